@@ -1,0 +1,184 @@
+/*
+ * misa.h - C ABI of the MI355X (gfx950) MISA indexer library.
+ *
+ * The library computes the token-selection ("indexer") stage of sparse
+ * attention as defined in "MISA: Mixture of Indexer Sparse Attention"
+ * (Preliminaries, "Indexer in DSA"; Method, "MISA: mixture of indexer
+ * experts" and "Hierarchical MISA").  Five calls, one per stage:
+ *
+ *   misa_pool_keys     Eq. pool                        block mean pooling
+ *   misa_route_heads   Eq. misa_route_score/misa_route top-h head routing
+ *   misa_score_tokens  Eq. misa_score (Eq. dsa_score)  routed token scoring
+ *   misa_topk          Eq. misa_topk/misa_candidate    top-k token selection
+ *   misa_rerank        Eq. misa_final_topk             dense re-rank (MISA-dagger)
+ *
+ * Conventions common to all calls
+ * -------------------------------
+ * - Every data pointer is DEVICE memory owned by the caller unless it is
+ *   marked "host".  The library allocates nothing, frees nothing and keeps
+ *   no state between calls.  Scratch memory is passed in as (ws, ws_bytes);
+ *   ask misa_workspace_bytes() for the size (it may be 0, then ws may be
+ *   NULL).  ws must be 256-byte aligned.
+ * - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   Calls only enqueue work on it; they never synchronise the host.
+ * - Tensors are dense, row-major, innermost dimension contiguous:
+ *     keys    K      [n_seq, L, d]       k_dtype
+ *     kscale         [n_seq, L]          float, only for MISA_FP8_E4M3 keys:
+ *                                        key value = kscale * decode(code);
+ *                                        scales must be finite and >= 0
+ *     queries Q      [n_seq, n_q, H, d]  q_dtype
+ *     gates   W      [n_seq, n_q, H]     float (any sign)
+ *   K, Q must be 16-byte aligned.
+ * - Causality: query t of sequence i sees the keys 0 .. n-1 with
+ *     len_i = seq_len ? clamp(seq_len[i], 0, L) : L
+ *     n     = q_pos  ? clamp(q_pos[t] + 1, 0, len_i) : len_i
+ *   (q_pos[t] is the 0-based position of query t; its own token is visible).
+ * - Ties (equal head importances, equal token scores) go to the lower
+ *   index; -0.0 and +0.0 are equal.  Index lists are returned in ascending
+ *   index order.  NaN inputs give unspecified selections.
+ * - Errors: every call validates its host-side arguments first and launches
+ *   nothing if validation fails.  The return value is a misa_status;
+ *   misa_last_error() returns a thread-local description of the last failure
+ *   on the calling thread.  Device data (q_pos, seq_len, heads, cand) cannot
+ *   be validated on the host: out-of-range values are clamped or ignored as
+ *   described per call, they never cause out-of-bounds accesses.
+ * - Limits of this build: d == 128, 1 <= H <= 64, 1 <= h <= H,
+ *   L <= 524288, k <= 16384, q_dtype in {F32, BF16}.
+ */
+#ifndef MISA_H
+#define MISA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum misa_status {
+  MISA_OK = 0,
+  MISA_ERR_INVALID_ARG = 1, /* NULL required pointer, size out of range            */
+  MISA_ERR_UNSUPPORTED = 2, /* legal request outside the limits of this build      */
+  MISA_ERR_WORKSPACE = 3,   /* ws NULL/misaligned or ws_bytes too small            */
+  MISA_ERR_HIP = 4          /* a HIP runtime call (launch) reported an error       */
+} misa_status;
+
+typedef enum misa_dtype {
+  MISA_F32 = 0,
+  MISA_BF16 = 1,
+  MISA_FP8_E4M3 = 2 /* OCP FP8 E4M3 ("e4m3fn": bias 7, max 448, no infinity), keys only */
+} misa_dtype;
+
+typedef enum misa_op {
+  MISA_OP_POOL = 0,
+  MISA_OP_ROUTE = 1,
+  MISA_OP_SCORE = 2,
+  MISA_OP_TOPK = 3,
+  MISA_OP_RERANK = 4
+} misa_op;
+
+/* Problem description shared by all calls (host struct, passed by pointer). */
+typedef struct misa_problem {
+  int32_t n_seq;          /* sequences in the batch, >= 1                             */
+  int32_t L;              /* keys stored per sequence (row count of K), >= 1          */
+  int32_t d;              /* indexer head dimension; must be 128                      */
+  int32_t n_q;            /* queries per sequence, >= 1                               */
+  int32_t H;              /* indexer heads H^I, 1..64                                 */
+  int32_t B;              /* router block size, >= 1 (any value, also >= L)           */
+  int32_t h;              /* active heads, 1..H                                       */
+  int32_t k_dtype;        /* misa_dtype of K                                          */
+  int32_t q_dtype;        /* misa_dtype of Q (F32 or BF16)                            */
+  const int32_t* q_pos;   /* device [n_q], shared by all sequences; NULL = decode:
+                             every query sits at the last position (n = len_i)       */
+  const int32_t* seq_len; /* device [n_seq] or NULL (every sequence holds L keys)     */
+} misa_problem;
+
+/* Bytes of scratch the given op needs for this problem.  `k` is the k of
+ * misa_topk, or k_cand of misa_rerank; ignored by the other ops.  Returns 0 on
+ * invalid input as well (the op itself will then report the error). */
+size_t misa_workspace_bytes(const misa_problem* p, int32_t op, int32_t k);
+
+/* Text of the last error raised on this thread ("" if none).  Never NULL. */
+const char* misa_last_error(void);
+
+/* Library/ABI version: major * 1000 + minor. */
+int32_t misa_version(void);
+
+/*
+ * Stage 1 - block mean pooling (Eq. pool; Method, "Block-pooled router").
+ * The stored keys of each sequence are cut into M = ceil(L / B) contiguous
+ * blocks; block b covers tokens b*B .. min((b+1)*B, len_i) - 1 and Kp[i, b, :]
+ * is the arithmetic mean of its (de-quantised) keys, fp32.  A partial last
+ * block is averaged over the tokens it holds; blocks entirely past len_i are
+ * written as zeros.
+ *   K       in   [n_seq, L, d]
+ *   kscale  in   [n_seq, L] (FP8 keys only, else NULL)
+ *   Kp      out  [n_seq, M, d] float
+ */
+misa_status misa_pool_keys(const misa_problem* p, const void* K, const float* kscale,
+                           float* Kp, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stage 2 - head routing (Eq. misa_route_score, Eq. misa_route).
+ * For every query:  A[j,b] = W[j] * ReLU(Q[j] . k~_b),
+ *                   E[j]   = (1/M_n) * sum_b |A[j,b]|,   M_n = ceil(n / B),
+ * and the h heads with the largest E are kept.  The blocks are those of the
+ * query's own visible prefix 0..n-1: complete blocks come from Kp; if
+ * n is not a multiple of B, the last block is the mean of keys
+ * floor(n/B)*B .. n-1 (read from K when n < len_i, so no pooled key ever
+ * contains a token the query cannot see).  n == 0 gives E = 0.
+ *   Q, W    in
+ *   Kp      in   [n_seq, M, d] float, as written by misa_pool_keys for the
+ *                same problem
+ *   K,kscale in  raw keys (used only for partial last blocks of causal queries)
+ *   heads   out  [n_seq, n_q, h] int32, ascending
+ *   E       out  [n_seq, n_q, H] float, may be NULL
+ */
+misa_status misa_route_heads(const misa_problem* p, const void* Q, const float* W,
+                             const float* Kp, const void* K, const float* kscale,
+                             int32_t* heads, float* E, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stage 3 - token scoring with the active heads (Eq. misa_score).
+ *   S[i,t,s] = sum_{j in heads[i,t,:]} W[j] * ReLU(Q[j] . k_s)   for s < n,
+ *   S[i,t,s] = -inf                                              for n <= s < L.
+ * heads == NULL scores with all H heads (h is ignored): the dense DSA indexer
+ * of Eq. dsa_score.  Head indices outside 0..H-1 contribute nothing; a head
+ * listed twice is counted twice.  Products of the stored bf16/fp8 values are
+ * exact; accumulation is fp32.
+ *   heads   in   [n_seq, n_q, h] int32 or NULL
+ *   S       out  [n_seq, n_q, L] float
+ */
+misa_status misa_score_tokens(const misa_problem* p, const void* Q, const float* W,
+                              const int32_t* heads, const void* K, const float* kscale,
+                              float* S, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stage 4 - top-k selection (Eq. misa_topk; with k = k' Eq. misa_candidate).
+ * Selects the min(k, n) largest entries of S[i,t,0..n-1]; exact, ties to the
+ * lower index.
+ *   S    in   [n_seq, n_q, L] float
+ *   idx  out  [n_seq, n_q, k] int32 ascending; unused tail slots = -1
+ *   val  out  [n_seq, n_q, k] float or NULL: val[j] = S[idx[j]], tail = -inf
+ */
+misa_status misa_topk(const misa_problem* p, const float* S, int32_t k, int32_t* idx,
+                      float* val, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stage 5 - MISA-dagger fine stage (Eq. misa_final_topk): re-score the
+ * candidates with ALL H heads (Eq. dsa_score) and keep the best k.
+ *   cand  in   [n_seq, n_q, k_cand] int32: distinct token indices in ascending
+ *              order as misa_topk writes them; entries < 0 or >= n are skipped
+ *   idx   out  [n_seq, n_q, k] int32 ascending, tail = -1
+ *   val   out  [n_seq, n_q, k] float or NULL (dense scores), tail = -inf
+ * Ties go to the earlier candidate slot (= lower token index for ascending
+ * cand).  Requires 1 <= k <= k_cand <= 16384.
+ */
+misa_status misa_rerank(const misa_problem* p, const void* Q, const float* W, const void* K,
+                        const float* kscale, const int32_t* cand, int32_t k_cand, int32_t k,
+                        int32_t* idx, float* val, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MISA_H */

@@ -1,0 +1,180 @@
+// C ABI of the MISA indexer library: argument validation, workspace sizing,
+// error reporting and dispatch to the kernel launchers.  See include/misa.h
+// for the contract of every entry point.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+misa_status fail(misa_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Validates the problem description and converts it for the kernels.
+misa_status check_problem(const misa_problem* p, misa::Prob* out) {
+  if (!p) return fail(MISA_ERR_INVALID_ARG, "problem is NULL");
+  if (p->n_seq < 1 || p->L < 1 || p->n_q < 1 || p->H < 1 || p->B < 1)
+    return fail(MISA_ERR_INVALID_ARG, "n_seq, L, n_q, H and B must all be >= 1 (got %d %d %d %d %d)",
+                p->n_seq, p->L, p->n_q, p->H, p->B);
+  if (p->h < 1 || p->h > p->H)
+    return fail(MISA_ERR_INVALID_ARG, "h must be in 1..H (h=%d, H=%d)", p->h, p->H);
+  if (p->k_dtype < MISA_F32 || p->k_dtype > MISA_FP8_E4M3)
+    return fail(MISA_ERR_INVALID_ARG, "unknown k_dtype %d", p->k_dtype);
+  if (p->q_dtype < MISA_F32 || p->q_dtype > MISA_FP8_E4M3)
+    return fail(MISA_ERR_INVALID_ARG, "unknown q_dtype %d", p->q_dtype);
+  if (p->n_q > 1 && !p->q_pos)
+    return fail(MISA_ERR_INVALID_ARG, "q_pos is required when n_q > 1");
+  if (p->d != misa::kD) return fail(MISA_ERR_UNSUPPORTED, "d must be 128 (got %d)", p->d);
+  if (p->H > misa::kMaxH) return fail(MISA_ERR_UNSUPPORTED, "H must be <= 64 (got %d)", p->H);
+  if (p->q_dtype == MISA_FP8_E4M3) return fail(MISA_ERR_UNSUPPORTED, "fp8 queries are not supported");
+  if (p->L > misa::kMaxRowLen) return fail(MISA_ERR_UNSUPPORTED, "L must be <= 524288 (got %d)", p->L);
+  if (p->n_seq > 65535 || p->n_q > 65535)
+    return fail(MISA_ERR_UNSUPPORTED, "n_seq and n_q must be <= 65535");
+  out->n_seq = p->n_seq; out->L = p->L; out->n_q = p->n_q; out->H = p->H; out->B = p->B;
+  out->h = p->h;
+  out->M = (int)(((long long)p->L + p->B - 1) / p->B);
+  out->q_pos = p->q_pos; out->seq_len = p->seq_len;
+  return MISA_OK;
+}
+
+misa_status check_keys(const misa_problem* p, const void* K, const float* kscale) {
+  if (!K) return fail(MISA_ERR_INVALID_ARG, "K is NULL");
+  if (!aligned(K, 16)) return fail(MISA_ERR_INVALID_ARG, "K must be 16-byte aligned");
+  if (p->k_dtype == MISA_FP8_E4M3 && !kscale)
+    return fail(MISA_ERR_INVALID_ARG, "kscale is required for fp8 keys");
+  return MISA_OK;
+}
+
+misa_status check_queries(const void* Q, const float* W) {
+  if (!Q || !W) return fail(MISA_ERR_INVALID_ARG, "Q or W is NULL");
+  if (!aligned(Q, 16)) return fail(MISA_ERR_INVALID_ARG, "Q must be 16-byte aligned");
+  return MISA_OK;
+}
+
+misa_status check_ws(size_t need, const void* ws, size_t ws_bytes) {
+  if (need == 0) return MISA_OK;
+  if (!ws) return fail(MISA_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", need);
+  if (!aligned(ws, 256)) return fail(MISA_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (ws_bytes < need)
+    return fail(MISA_ERR_WORKSPACE, "workspace too small: %zu bytes given, %zu needed", ws_bytes, need);
+  return MISA_OK;
+}
+
+misa_status hip_result(hipError_t e, const char* what) {
+  if (e == hipSuccess) { g_err[0] = 0; return MISA_OK; }
+  return fail(MISA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+size_t ws_bytes_for(const misa::Prob& pr, int op, int k) {
+  switch (op) {
+    case MISA_OP_ROUTE: return misa::route_ws_bytes(pr);
+    case MISA_OP_RERANK:
+      return k >= 1 ? (size_t)pr.n_seq * pr.n_q * (size_t)k * sizeof(float) : 0;
+    default: return 0;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t misa_version(void) { return 1000; }
+
+const char* misa_last_error(void) { return g_err; }
+
+size_t misa_workspace_bytes(const misa_problem* p, int32_t op, int32_t k) {
+  misa::Prob pr;
+  if (check_problem(p, &pr) != MISA_OK) return 0;
+  if (op < MISA_OP_POOL || op > MISA_OP_RERANK) return 0;
+  return ws_bytes_for(pr, op, k);
+}
+
+misa_status misa_pool_keys(const misa_problem* p, const void* K, const float* kscale, float* Kp,
+                           void* ws, size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  misa::Prob pr;
+  misa_status st = check_problem(p, &pr);
+  if (st != MISA_OK) return st;
+  if ((st = check_keys(p, K, kscale)) != MISA_OK) return st;
+  if (!Kp) return fail(MISA_ERR_INVALID_ARG, "Kp is NULL");
+  return hip_result(misa::launch_pool(pr, p->k_dtype, K, kscale, Kp, (hipStream_t)stream),
+                    "misa_pool_keys launch");
+}
+
+misa_status misa_route_heads(const misa_problem* p, const void* Q, const float* W, const float* Kp,
+                             const void* K, const float* kscale, int32_t* heads, float* E, void* ws,
+                             size_t ws_bytes, void* stream) {
+  misa::Prob pr;
+  misa_status st = check_problem(p, &pr);
+  if (st != MISA_OK) return st;
+  if ((st = check_queries(Q, W)) != MISA_OK) return st;
+  if ((st = check_keys(p, K, kscale)) != MISA_OK) return st;
+  if (!Kp || !heads) return fail(MISA_ERR_INVALID_ARG, "Kp or heads is NULL");
+  if ((st = check_ws(ws_bytes_for(pr, MISA_OP_ROUTE, 0), ws, ws_bytes)) != MISA_OK) return st;
+  return hip_result(misa::launch_route(pr, p->k_dtype, p->q_dtype, Q, W, Kp, K, kscale, heads, E, ws,
+                                       (hipStream_t)stream),
+                    "misa_route_heads launch");
+}
+
+misa_status misa_score_tokens(const misa_problem* p, const void* Q, const float* W,
+                              const int32_t* heads, const void* K, const float* kscale, float* S,
+                              void* ws, size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  misa::Prob pr;
+  misa_status st = check_problem(p, &pr);
+  if (st != MISA_OK) return st;
+  if ((st = check_queries(Q, W)) != MISA_OK) return st;
+  if ((st = check_keys(p, K, kscale)) != MISA_OK) return st;
+  if (!S) return fail(MISA_ERR_INVALID_ARG, "S is NULL");
+  return hip_result(misa::launch_score(pr, p->k_dtype, p->q_dtype, Q, W, heads, K, kscale, nullptr, 0,
+                                       S, (hipStream_t)stream),
+                    "misa_score_tokens launch");
+}
+
+misa_status misa_topk(const misa_problem* p, const float* S, int32_t k, int32_t* idx, float* val,
+                      void* ws, size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  misa::Prob pr;
+  misa_status st = check_problem(p, &pr);
+  if (st != MISA_OK) return st;
+  if (!S || !idx) return fail(MISA_ERR_INVALID_ARG, "S or idx is NULL");
+  if (k < 1) return fail(MISA_ERR_INVALID_ARG, "k must be >= 1 (got %d)", k);
+  if (k > misa::kMaxTopK) return fail(MISA_ERR_UNSUPPORTED, "k must be <= 16384 (got %d)", k);
+  return hip_result(misa::launch_topk(pr, S, pr.L, k, nullptr, idx, val, (hipStream_t)stream),
+                    "misa_topk launch");
+}
+
+misa_status misa_rerank(const misa_problem* p, const void* Q, const float* W, const void* K,
+                        const float* kscale, const int32_t* cand, int32_t k_cand, int32_t k,
+                        int32_t* idx, float* val, void* ws, size_t ws_bytes, void* stream) {
+  misa::Prob pr;
+  misa_status st = check_problem(p, &pr);
+  if (st != MISA_OK) return st;
+  if ((st = check_queries(Q, W)) != MISA_OK) return st;
+  if ((st = check_keys(p, K, kscale)) != MISA_OK) return st;
+  if (!cand || !idx) return fail(MISA_ERR_INVALID_ARG, "cand or idx is NULL");
+  if (k < 1 || k_cand < k)
+    return fail(MISA_ERR_INVALID_ARG, "need 1 <= k <= k_cand (k=%d, k_cand=%d)", k, k_cand);
+  if (k_cand > misa::kMaxTopK)
+    return fail(MISA_ERR_UNSUPPORTED, "k_cand must be <= 16384 (got %d)", k_cand);
+  if ((st = check_ws(ws_bytes_for(pr, MISA_OP_RERANK, k_cand), ws, ws_bytes)) != MISA_OK) return st;
+  float* dense = static_cast<float*>(ws);
+  hipError_t e = misa::launch_score(pr, p->k_dtype, p->q_dtype, Q, W, nullptr, K, kscale, cand, k_cand,
+                                    dense, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_result(e, "misa_rerank score launch");
+  return hip_result(misa::launch_topk(pr, dense, k_cand, k, cand, idx, val, (hipStream_t)stream),
+                    "misa_rerank top-k launch");
+}
+
+}  // extern "C"

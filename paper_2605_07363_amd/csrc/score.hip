@@ -1,0 +1,260 @@
+// Stage 3: token scoring with the routed heads (Eq. misa_score; with all heads
+// Eq. dsa_score).  Also used for the candidate re-scoring of Eq. misa_final_topk.
+//
+// score_stream_kernel (bf16 queries, bf16 or fp8 keys, whole-cache scoring):
+//   the decode hot loop.  Every key byte is read exactly once, straight from
+//   HBM into registers: a wavefront takes 64 consecutive keys per step as four
+//   16-key tiles, each lane loading one contiguous quarter row.  The h dot
+//   products per key are evaluated by the matrix core as a 16-row (heads,
+//   zero-padded) x 16-column (keys) x 128 product (v_mfma_f32_16x16x32_bf16),
+//   which keeps the vector ALU nearly idle so that the kernel stays bound by
+//   HBM; fp8 codes are widened to bf16 exactly and the per-token scale is
+//   applied after the head sum (ReLU(c x) = c ReLU(x) for c >= 0).  The sum
+//   over heads is in-lane for the four rows a lane holds and then a two-step
+//   exchange across the four 16-lane groups that leaves lane i with the score
+//   of key i of the 64-key group, so stores are fully coalesced.
+//
+// score_generic_kernel: plain fp32 FMA path for every other combination
+//   (fp32 inputs, candidate lists).  One thread per key or candidate; the
+//   gathered query heads sit in LDS and are read by broadcast.
+#include "kernels.h"
+
+namespace misa {
+
+// ------------------------------------------------------------------ generic
+template <int KDT, int QDT>
+__global__ __launch_bounds__(256) void score_generic_kernel(
+    Prob p, const void* __restrict__ Q, const float* __restrict__ W, const int* __restrict__ heads,
+    const void* __restrict__ K, const float* __restrict__ kscale, const int* __restrict__ cand,
+    int k_cand, float* __restrict__ out) {
+  __shared__ float qs[kMaxH][kD];
+  __shared__ float wsm[kMaxH];
+  using KV = Vec16<KDT>;
+  using QV = Vec16<QDT>;
+  const int t = blockIdx.y, seq = blockIdx.z, tid = threadIdx.x;
+  const int n = visible(p, seq, t);
+  const int hc = heads ? p.h : p.H;
+  const int hpad = (hc + 7) & ~7;
+  const size_t qrow = (size_t)seq * p.n_q + t;
+
+  // Gather the active heads (zero rows for padding and for invalid indices).
+  for (int i = tid; i < hpad * (kD / QV::N); i += 256) {
+    const int j = i / (kD / QV::N), c = i % (kD / QV::N);
+    int head = -1;
+    if (j < hc) head = heads ? heads[qrow * p.h + j] : j;
+    float v[QV::N];
+    if (head >= 0 && head < p.H) {
+      QV::load(static_cast<const char*>(Q) + ((qrow * p.H + head) * kD + c * QV::N) * (QV::ROW_BYTES / kD), v);
+    } else {
+#pragma unroll
+      for (int e = 0; e < QV::N; ++e) v[e] = 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < QV::N; ++e) qs[j][c * QV::N + e] = v[e];
+  }
+  for (int j = tid; j < hpad; j += 256) {
+    int head = -1;
+    if (j < hc) head = heads ? heads[qrow * p.h + j] : j;
+    wsm[j] = (head >= 0 && head < p.H) ? W[qrow * p.H + head] : 0.f;
+  }
+  __syncthreads();
+
+  const int row_len = cand ? k_cand : p.L;
+  const int slot = blockIdx.x * 256 + tid;
+  if (slot >= row_len) return;
+  const int s = cand ? cand[qrow * k_cand + slot] : slot;
+  float result = -INFINITY;
+  if (s >= 0 && s < n) {
+    const char* krow = static_cast<const char*>(K) + ((size_t)seq * p.L + s) * KV::ROW_BYTES;
+    float total = 0.f;
+    for (int hg = 0; hg < hpad; hg += 8) {
+      float acc[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+      for (int c = 0; c < kD / KV::N; ++c) {
+        float kv[KV::N];
+        KV::load(krow + c * 16, kv);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+#pragma unroll
+          for (int e = 0; e < KV::N; ++e) acc[j] = fmaf(qs[hg + j][c * KV::N + e], kv[e], acc[j]);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) total = fmaf(wsm[hg + j], fmaxf(acc[j], 0.f), total);
+    }
+    if (KDT == MISA_FP8_E4M3) total *= kscale[(size_t)seq * p.L + s];
+    result = total;
+  }
+  out[qrow * row_len + slot] = result;
+}
+
+// ------------------------------------------------------------------ streaming
+// Widen 4 packed fp8 codes to 4 bf16 (exact: 3 mantissa bits fit in 7).
+__device__ __forceinline__ void fp8x4_to_bf16x4(uint32_t w, uint32_t& lo, uint32_t& hi) {
+  const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(w, false);
+  const f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8(w, true);
+  // take the upper halves of the two floats: bf16 pair (first value in the low half)
+  lo = __builtin_amdgcn_perm(__float_as_uint(a[1]), __float_as_uint(a[0]), 0x07060302u);
+  hi = __builtin_amdgcn_perm(__float_as_uint(b[1]), __float_as_uint(b[0]), 0x07060302u);
+}
+
+union Frag {
+  bf16x8 v;
+  uint4 u;
+  uint32_t w[4];
+};
+
+// NT = 16-row head tiles (heads <= 16 * NT).
+template <int KDT, int NT>
+__global__ __launch_bounds__(256) void score_stream_kernel(
+    Prob p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
+    const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
+    float* __restrict__ S) {
+  constexpr int ROW_BYTES = KDT == MISA_BF16 ? 256 : 128;
+  constexpr int LANE_BYTES = ROW_BYTES / 4;  // one quarter row per lane
+  const int t = blockIdx.y, seq = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int n = visible(p, seq, t);
+  const int hc = heads ? p.h : p.H;
+  const size_t qrow = (size_t)seq * p.n_q + t;
+
+  // A operand: head rows.  Lane (c, g) holds, for k-step i, the 8 components
+  // 32 g + 8 i .. + 7 of head row c of each tile; the key fragments use the
+  // same component mapping, so the contraction runs over all 128.
+  Frag a[NT][4];
+  float wv[NT][4];
+#pragma unroll
+  for (int T = 0; T < NT; ++T) {
+    const int r = T * 16 + c;
+    int head = -1;
+    if (r < hc) head = heads ? heads[qrow * p.h + r] : r;
+    if (head >= 0 && head < p.H) {
+      const uint4* src = reinterpret_cast<const uint4*>(Q + (qrow * p.H + head) * kD + 32 * g);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[T][i].u = src[i];
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[T][i].u = make_uint4(0, 0, 0, 0);
+    }
+    // The accumulator of lane (c, g) holds head rows 4 g + j (j = 0..3) for key column c.
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int rr = T * 16 + 4 * g + j;
+      int hd = -1;
+      if (rr < hc) hd = heads ? heads[qrow * p.h + rr] : rr;
+      wv[T][j] = (hd >= 0 && hd < p.H) ? W[qrow * p.H + hd] : 0.f;
+    }
+  }
+
+  const char* kbase = static_cast<const char*>(K) + (size_t)seq * p.L * ROW_BYTES;
+  float* srow = S + qrow * p.L;
+  const int k_begin = blockIdx.x * keys_per_wg;
+  const int k_end = min(k_begin + keys_per_wg, p.L);
+
+  for (int kg = k_begin + wave * 64; kg < k_end; kg += 256) {
+    const int key = kg + lane;  // the key this lane finally owns
+    if (kg >= n) {              // whole group invisible
+      if (key < p.L) srow[key] = -INFINITY;
+      continue;
+    }
+    // Load four 16-key tiles (rows clamped into the visible prefix: n >= 1 here).
+    Frag b[4][4];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+      const int row = min(kg + tt * 16 + c, n - 1);
+      const char* src = kbase + (size_t)row * ROW_BYTES + g * LANE_BYTES;
+      if (KDT == MISA_BF16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) b[tt][i].u = reinterpret_cast<const uint4*>(src)[i];
+      } else {
+        const uint4 lo = reinterpret_cast<const uint4*>(src)[0];
+        const uint4 hi = reinterpret_cast<const uint4*>(src)[1];
+        const uint32_t w8[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          fp8x4_to_bf16x4(w8[2 * i], b[tt][i].w[0], b[tt][i].w[1]);
+          fp8x4_to_bf16x4(w8[2 * i + 1], b[tt][i].w[2], b[tt][i].w[3]);
+        }
+      }
+    }
+    float scale = 1.f;
+    if (KDT == MISA_FP8_E4M3) scale = kscale[(size_t)seq * p.L + min(key, n - 1)];
+
+    float part[4];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+      float s = 0.f;
+#pragma unroll
+      for (int T = 0; T < NT; ++T) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[T][i].v, b[tt][i].v, acc, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s = fmaf(wv[T][j], fmaxf(acc[j], 0.f), s);
+      }
+      part[tt] = s;
+    }
+    // Sum over the four lane groups so that group g ends with tile g.
+    const bool up2 = (g & 2) != 0, up1 = (g & 1) != 0;
+    const float r0 = __shfl_xor(up2 ? part[0] : part[2], 32);
+    const float r1 = __shfl_xor(up2 ? part[1] : part[3], 32);
+    const float k0 = (up2 ? part[2] : part[0]) + r0;
+    const float k1 = (up2 ? part[3] : part[1]) + r1;
+    const float r2 = __shfl_xor(up1 ? k0 : k1, 16);
+    const float fin = (up1 ? k1 : k0) + r2;
+    if (key < p.L) srow[key] = key < n ? fin * scale : -INFINITY;
+  }
+}
+
+template <int KDT, int QDT>
+static hipError_t launch_generic(const Prob& p, const void* Q, const float* W, const int* heads,
+                                 const void* K, const float* kscale, const int* cand, int k_cand,
+                                 float* out, hipStream_t st) {
+  const int row_len = cand ? k_cand : p.L;
+  const dim3 grid((row_len + 255) / 256, p.n_q, p.n_seq);
+  score_generic_kernel<KDT, QDT><<<grid, 256, 0, st>>>(p, Q, W, heads, K, kscale, cand, k_cand, out);
+  return hipGetLastError();
+}
+
+template <int KDT>
+static hipError_t launch_stream(const Prob& p, const void* Q, const float* W, const int* heads,
+                                const void* K, const float* kscale, float* S, hipStream_t st) {
+  const int hc = heads ? p.h : p.H;
+  const int nt = (hc + 15) / 16;
+  const int keys_per_wg = 1024;
+  const dim3 grid((p.L + keys_per_wg - 1) / keys_per_wg, p.n_q, p.n_seq);
+  const uint16_t* q = static_cast<const uint16_t*>(Q);
+#define GO(NT) score_stream_kernel<KDT, NT><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S)
+  switch (nt) {
+    case 1: GO(1); break;
+    case 2: GO(2); break;
+    case 3: GO(3); break;
+    default: GO(4); break;
+  }
+#undef GO
+  return hipGetLastError();
+}
+
+hipError_t launch_score(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,
+                        const int* heads, const void* K, const float* kscale, const int* cand,
+                        int k_cand, float* out, hipStream_t st) {
+  if (!cand && q_dtype == MISA_BF16 && k_dtype == MISA_BF16)
+    return launch_stream<MISA_BF16>(p, Q, W, heads, K, kscale, out, st);
+  if (!cand && q_dtype == MISA_BF16 && k_dtype == MISA_FP8_E4M3)
+    return launch_stream<MISA_FP8_E4M3>(p, Q, W, heads, K, kscale, out, st);
+#define GEN(KD, QD) return launch_generic<KD, QD>(p, Q, W, heads, K, kscale, cand, k_cand, out, st)
+  if (q_dtype == MISA_F32) {
+    if (k_dtype == MISA_F32) GEN(MISA_F32, MISA_F32);
+    if (k_dtype == MISA_BF16) GEN(MISA_BF16, MISA_F32);
+    GEN(MISA_FP8_E4M3, MISA_F32);
+  }
+  if (k_dtype == MISA_F32) GEN(MISA_F32, MISA_BF16);
+  if (k_dtype == MISA_BF16) GEN(MISA_BF16, MISA_BF16);
+  GEN(MISA_FP8_E4M3, MISA_BF16);
+#undef GEN
+}
+
+}  // namespace misa

@@ -1,0 +1,229 @@
+"""ctypes binding of libmisa.so (see include/misa.h for the contract).
+
+Argument marshalling only: every stage of the indexer runs in the HIP kernels
+of the library.  torch is used for device memory and streams.  Importing this
+module fails if the library has not been built; there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmisa.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2605_07363_amd.build` "
+        "(there is no fallback path)")
+lib = ctypes.CDLL(LIB_PATH)
+
+F32, BF16, FP8_E4M3 = 0, 1, 2
+DTYPE_CODES = {"f32": F32, "bf16": BF16, "e4m3": FP8_E4M3}
+OP_POOL, OP_ROUTE, OP_SCORE, OP_TOPK, OP_RERANK = range(5)
+STATUS_NAMES = {0: "MISA_OK", 1: "MISA_ERR_INVALID_ARG", 2: "MISA_ERR_UNSUPPORTED",
+                3: "MISA_ERR_WORKSPACE", 4: "MISA_ERR_HIP"}
+
+
+class misa_problem(ctypes.Structure):
+    _fields_ = [("n_seq", ctypes.c_int32), ("L", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("n_q", ctypes.c_int32), ("H", ctypes.c_int32), ("B", ctypes.c_int32),
+                ("h", ctypes.c_int32), ("k_dtype", ctypes.c_int32), ("q_dtype", ctypes.c_int32),
+                ("q_pos", ctypes.c_void_p), ("seq_len", ctypes.c_void_p)]
+
+
+_P = ctypes.POINTER(misa_problem)
+_V = ctypes.c_void_p
+lib.misa_version.restype = ctypes.c_int32
+lib.misa_last_error.restype = ctypes.c_char_p
+lib.misa_workspace_bytes.restype = ctypes.c_size_t
+lib.misa_workspace_bytes.argtypes = [_P, ctypes.c_int32, ctypes.c_int32]
+lib.misa_pool_keys.restype = ctypes.c_int
+lib.misa_pool_keys.argtypes = [_P, _V, _V, _V, _V, ctypes.c_size_t, _V]
+lib.misa_route_heads.restype = ctypes.c_int
+lib.misa_route_heads.argtypes = [_P, _V, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]
+lib.misa_score_tokens.restype = ctypes.c_int
+lib.misa_score_tokens.argtypes = [_P, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]
+lib.misa_topk.restype = ctypes.c_int
+lib.misa_topk.argtypes = [_P, _V, ctypes.c_int32, _V, _V, _V, ctypes.c_size_t, _V]
+lib.misa_rerank.restype = ctypes.c_int
+lib.misa_rerank.argtypes = [_P, _V, _V, _V, _V, _V, ctypes.c_int32, ctypes.c_int32, _V, _V, _V,
+                            ctypes.c_size_t, _V]
+
+
+class MisaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise MisaError(status, lib.misa_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors passed to the library must be contiguous device tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(ws: Optional[torch.Tensor]):
+    if ws is None:
+        return None, 0
+    return _ptr(ws), ws.numel() * ws.element_size()
+
+
+@dataclass
+class Problem:
+    """Host description of one indexer problem (mirrors struct misa_problem)."""
+    n_seq: int
+    L: int
+    n_q: int
+    H: int
+    B: int
+    h: int
+    k_dtype: int
+    q_dtype: int
+    q_pos: Optional[torch.Tensor] = None     # int32 device [n_q] or None (decode)
+    seq_len: Optional[torch.Tensor] = None   # int32 device [n_seq] or None
+    d: int = 128
+
+    @property
+    def M(self) -> int:
+        return -(-self.L // self.B)
+
+    def c(self) -> misa_problem:
+        for t in (self.q_pos, self.seq_len):
+            if t is not None and (t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous()):
+                raise ValueError("q_pos / seq_len must be contiguous int32 device tensors")
+        return misa_problem(self.n_seq, self.L, self.d, self.n_q, self.H, self.B, self.h,
+                            self.k_dtype, self.q_dtype,
+                            self.q_pos.data_ptr() if self.q_pos is not None else None,
+                            self.seq_len.data_ptr() if self.seq_len is not None else None)
+
+
+def version() -> int:
+    return lib.misa_version()
+
+
+def workspace_bytes(p: Problem, op: int, k: int = 0) -> int:
+    return lib.misa_workspace_bytes(ctypes.byref(p.c()), op, k)
+
+
+def alloc_workspace(p: Problem, op: int, k: int = 0, device="cuda") -> Optional[torch.Tensor]:
+    n = workspace_bytes(p, op, k)
+    return torch.empty(n, dtype=torch.uint8, device=device) if n else None
+
+
+def pool_keys(p: Problem, K, kscale, Kp, ws=None) -> None:
+    w, wb = _ws(ws)
+    _check(lib.misa_pool_keys(ctypes.byref(p.c()), _ptr(K), _ptr(kscale), _ptr(Kp), w, wb, _stream()))
+
+
+def route_heads(p: Problem, Q, W, Kp, K, kscale, heads, E=None, ws=None) -> None:
+    w, wb = _ws(ws)
+    _check(lib.misa_route_heads(ctypes.byref(p.c()), _ptr(Q), _ptr(W), _ptr(Kp), _ptr(K), _ptr(kscale),
+                                _ptr(heads), _ptr(E), w, wb, _stream()))
+
+
+def score_tokens(p: Problem, Q, W, heads, K, kscale, S, ws=None) -> None:
+    w, wb = _ws(ws)
+    _check(lib.misa_score_tokens(ctypes.byref(p.c()), _ptr(Q), _ptr(W), _ptr(heads), _ptr(K),
+                                 _ptr(kscale), _ptr(S), w, wb, _stream()))
+
+
+def topk(p: Problem, S, k: int, idx, val=None, ws=None) -> None:
+    w, wb = _ws(ws)
+    _check(lib.misa_topk(ctypes.byref(p.c()), _ptr(S), k, _ptr(idx), _ptr(val), w, wb, _stream()))
+
+
+def rerank(p: Problem, Q, W, K, kscale, cand, k_cand: int, k: int, idx, val=None, ws=None) -> None:
+    w, wb = _ws(ws)
+    _check(lib.misa_rerank(ctypes.byref(p.c()), _ptr(Q), _ptr(W), _ptr(K), _ptr(kscale), _ptr(cand),
+                           k_cand, k, _ptr(idx), _ptr(val), w, wb, _stream()))
+
+
+# ---------------------------------------------------------------------------
+# Plumbing helpers: device copies of generated inputs and preallocated buffers.
+# ---------------------------------------------------------------------------
+def to_device(inp: dict, device="cuda") -> dict:
+    """Raw numpy inputs (see workloads.make_inputs) -> device tensors + Problem."""
+    import numpy as np
+    wl = inp["wl"]
+
+    def dev(x, kind):
+        if x is None:
+            return None
+        if kind == "bf16":
+            return torch.from_numpy(x.view(np.int16)).to(device).view(torch.bfloat16)
+        return torch.from_numpy(x).to(device)
+
+    out = {
+        "K": dev(inp["K"], wl.k_dtype), "kscale": dev(inp["kscale"], "f32"),
+        "Q": dev(inp["Q"], wl.q_dtype), "W": dev(inp["W"], "f32"),
+        "q_pos": dev(inp["q_pos"], "i32"), "seq_len": dev(inp["seq_len"], "i32"),
+    }
+    out["problem"] = Problem(wl.n_seq, wl.L, wl.n_q, wl.H, wl.B, wl.h, DTYPE_CODES[wl.k_dtype],
+                             DTYPE_CODES[wl.q_dtype], out["q_pos"], out["seq_len"])
+    return out
+
+
+class Indexer:
+    """Preallocated outputs + workspaces for one problem; runs the stages in order."""
+
+    def __init__(self, p: Problem, k: int, k_cand: int = 0, device="cuda", want_E=False, want_val=False):
+        self.p, self.k, self.k_cand = p, k, k_cand
+        rows = (p.n_seq, p.n_q)
+        self.Kp = torch.empty((p.n_seq, p.M, p.d), dtype=torch.float32, device=device)
+        self.heads = torch.empty(rows + (p.h,), dtype=torch.int32, device=device)
+        self.E = torch.empty(rows + (p.H,), dtype=torch.float32, device=device) if want_E else None
+        self.S = torch.empty(rows + (p.L,), dtype=torch.float32, device=device)
+        k1 = k_cand if k_cand else k
+        self.idx1 = torch.empty(rows + (k1,), dtype=torch.int32, device=device)
+        self.val1 = torch.empty(rows + (k1,), dtype=torch.float32, device=device) if want_val else None
+        self.idx = self.idx1
+        self.val = self.val1
+        if k_cand:
+            self.idx = torch.empty(rows + (k,), dtype=torch.int32, device=device)
+            self.val = torch.empty(rows + (k,), dtype=torch.float32, device=device) if want_val else None
+        self.ws = {op: alloc_workspace(p, op, k1 if op == OP_TOPK else k_cand, device)
+                   for op in (OP_POOL, OP_ROUTE, OP_SCORE, OP_TOPK, OP_RERANK)
+                   if op != OP_RERANK or k_cand}
+
+    def pool(self, K, kscale):
+        pool_keys(self.p, K, kscale, self.Kp, self.ws[OP_POOL])
+
+    def route(self, Q, W, K, kscale):
+        route_heads(self.p, Q, W, self.Kp, K, kscale, self.heads, self.E, self.ws[OP_ROUTE])
+
+    def score(self, Q, W, K, kscale, dense=False):
+        score_tokens(self.p, Q, W, None if dense else self.heads, K, kscale, self.S, self.ws[OP_SCORE])
+
+    def select(self):
+        topk(self.p, self.S, self.k_cand if self.k_cand else self.k, self.idx1, self.val1,
+             self.ws[OP_TOPK])
+
+    def refine(self, Q, W, K, kscale):
+        rerank(self.p, Q, W, K, kscale, self.idx1, self.k_cand, self.k, self.idx, self.val,
+               self.ws[OP_RERANK])
+
+    def run(self, K, kscale, Q, W, pool=True):
+        """One pass of the whole indexer; returns the selected token indices."""
+        if pool:
+            self.pool(K, kscale)
+        self.route(Q, W, K, kscale)
+        self.score(Q, W, K, kscale)
+        self.select()
+        if self.k_cand:
+            self.refine(Q, W, K, kscale)
+        return self.idx

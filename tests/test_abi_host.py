@@ -1,0 +1,91 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before launching."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def misa():
+    from paper_2605_07363_amd import misa as m
+    return m
+
+
+def test_every_declared_symbol_is_exported(misa):
+    header = open(os.path.join(ROOT, "include", "misa.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(misa_[a-z_]+)\s*\(", header))
+    assert {"misa_pool_keys", "misa_route_heads", "misa_score_tokens", "misa_topk", "misa_rerank",
+            "misa_workspace_bytes", "misa_last_error", "misa_version"} <= names
+    for n in names:
+        assert hasattr(misa.lib, n), f"{n} declared in misa.h but not exported"
+    assert misa.version() == 1000
+
+
+def _prob(misa, **kw):
+    base = dict(n_seq=2, L=1000, n_q=1, H=64, B=64, h=8, k_dtype=misa.BF16, q_dtype=misa.BF16)
+    base.update(kw)
+    return misa.Problem(**base)
+
+
+FAKE = ctypes.c_void_p(0x1000)   # 16- and 256-byte aligned, never dereferenced on the host
+
+
+def _pool(misa, p, K=FAKE, kscale=None, Kp=FAKE):
+    return misa.lib.misa_pool_keys(ctypes.byref(p.c()), K, kscale, Kp, None, 0, None)
+
+
+def test_invalid_problem_fields_are_rejected_without_launch(misa):
+    INVALID, UNSUPPORTED = 1, 2
+    for kw in (dict(n_seq=0), dict(L=0), dict(n_q=0), dict(H=0), dict(B=0), dict(h=0), dict(h=65, H=64),
+               dict(k_dtype=7), dict(q_dtype=-1), dict(n_q=2)):   # n_q > 1 without q_pos
+        assert _pool(misa, _prob(misa, **kw)) == INVALID, kw
+        assert misa.lib.misa_last_error() != b""
+    for kw in (dict(d=64), dict(H=128, h=8), dict(q_dtype=misa.FP8_E4M3), dict(L=1 << 20),
+               dict(n_seq=70000)):
+        assert _pool(misa, _prob(misa, **kw)) == UNSUPPORTED, kw
+    assert misa.lib.misa_pool_keys(None, FAKE, None, FAKE, None, 0, None) == INVALID
+
+
+def test_null_and_misaligned_pointers(misa):
+    p = _prob(misa)
+    assert _pool(misa, p, K=None) == 1
+    assert _pool(misa, p, Kp=None) == 1
+    assert _pool(misa, p, K=ctypes.c_void_p(0x1008)) == 1
+    assert b"aligned" in misa.lib.misa_last_error()
+    assert _pool(misa, _prob(misa, k_dtype=misa.FP8_E4M3), kscale=None) == 1     # fp8 needs scales
+    pc = ctypes.byref(p.c())
+    assert misa.lib.misa_score_tokens(pc, None, FAKE, None, FAKE, None, FAKE, None, 0, None) == 1
+    assert misa.lib.misa_score_tokens(pc, FAKE, FAKE, None, FAKE, None, None, None, 0, None) == 1
+    assert misa.lib.misa_topk(pc, FAKE, 0, FAKE, None, None, 0, None) == 1          # k < 1
+    assert misa.lib.misa_topk(pc, FAKE, 20000, FAKE, None, None, 0, None) == 2      # k too large
+    assert misa.lib.misa_topk(pc, None, 8, FAKE, None, None, 0, None) == 1
+    assert misa.lib.misa_rerank(pc, FAKE, FAKE, FAKE, None, FAKE, 4, 8, FAKE, None, FAKE, 1 << 20, None) == 1  # k > k_cand
+    assert misa.lib.misa_rerank(pc, FAKE, FAKE, FAKE, None, None, 8, 4, FAKE, None, FAKE, 1 << 20, None) == 1
+
+
+def test_workspace_contract(misa):
+    p = _prob(misa)
+    pc = ctypes.byref(p.c())
+    need = misa.workspace_bytes(p, misa.OP_ROUTE)
+    assert need > 0 and need % 256 == 0
+    assert misa.workspace_bytes(p, misa.OP_POOL) == 0
+    assert misa.workspace_bytes(p, misa.OP_RERANK, 512) == 2 * 1 * 512 * 4
+    assert misa.workspace_bytes(p, 9) == 0
+    args = (pc, FAKE, FAKE, FAKE, FAKE, None, FAKE, None)
+    assert misa.lib.misa_route_heads(*args, None, 0, None) == 3                      # NULL workspace
+    assert misa.lib.misa_route_heads(*args, FAKE, need - 1, None) == 3               # too small
+    assert b"too small" in misa.lib.misa_last_error()
+    assert misa.lib.misa_route_heads(*args, ctypes.c_void_p(0x1010), need, None) == 3   # misaligned
+    assert misa.lib.misa_rerank(pc, FAKE, FAKE, FAKE, None, FAKE, 512, 64, FAKE, None, FAKE, 100, None) == 3
+
+
+def test_binding_refuses_host_tensors(misa):
+    import torch
+    p = _prob(misa)
+    with pytest.raises(ValueError):
+        misa.pool_keys(p, torch.zeros(4), None, torch.zeros(4))

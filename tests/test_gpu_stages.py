@@ -1,0 +1,259 @@
+"""GPU parity of each C-ABI call in isolation: every stage is fed
+oracle-produced inputs and compared with the oracle element by element."""
+import numpy as np
+import pytest
+
+from oracle import misa_oracle as O
+from paper_2605_07363_amd import workloads as WL
+from helpers import assert_scores_close, check_index_set, oracle_view
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def misa():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2605_07363_amd import misa as m
+    return m
+
+
+def small(name, **kw):
+    return WL.scaled(WL.WORKLOADS[name], **kw)
+
+
+CASES = {
+    # spans several tiles and a ragged tail; every dtype combination
+    "f32_decode": small("c0", L=1500, B=64),
+    "bf16_decode": small("c1", n_seq=3, L=5000, B=64, k=300),
+    "fp8_decode": small("c3", n_seq=2, L=4133, B=128, k=300, needles=16),
+    "bf16_prefill": small("c2", L=3000, n_q=70, B=64, k=200),
+    "fp8_prefill": small("c4", L=2500, n_q=40, B=64, k=128, k_cand=512, needles=16),
+    "f32_prefill": WL.scaled(WL.WORKLOADS["c0"], L=700, n_q=9, decode=False, B=50, k=64, needles=4),
+    "bf16_bigB": small("c1", n_seq=2, L=3000, B=5000, k=100),
+    "bf16_B1": small("c1", n_seq=1, L=300, B=1, k=50, needles=4),
+    "glm_dense_h": small("c3", n_seq=1, L=2000, h=32, B=128, k=100, needles=8),
+}
+
+
+def gen(name, seq_len=None):
+    return WL.make_inputs(CASES[name], seed=1234 + sum(map(ord, name)), seq_len=seq_len)
+
+
+def ragged(wl):
+    rng = np.random.default_rng(5)
+    lens = rng.integers(1, wl.L + 1, wl.n_seq)
+    lens[0] = wl.L
+    return lens.astype(np.int32)
+
+
+# --------------------------------------------------------------------- pool
+@pytest.mark.parametrize("name", ["f32_decode", "bf16_decode", "fp8_decode", "bf16_bigB", "bf16_B1"])
+@pytest.mark.parametrize("use_len", [False, True])
+def test_pool_keys(misa, name, use_len):
+    wl = CASES[name]
+    inp = gen(name, ragged(wl) if use_len else None)
+    dv = misa.to_device(inp)
+    p = dv["problem"]
+    Kp = torch.full((wl.n_seq, p.M, wl.d), 7.0, dtype=torch.float32, device="cuda")
+    misa.pool_keys(p, dv["K"], dv["kscale"], Kp)
+    got = Kp.cpu().numpy()
+    for s in range(wl.n_seq):
+        K, _, _, n = oracle_view(inp, s, 0)
+        ref = O.pool_keys(K, wl.B, n)
+        assert_scores_close(got[s, :ref.shape[0]], ref, f"pool {name} seq {s}")
+        assert not got[s, ref.shape[0]:].any()          # blocks past the sequence end are zero
+
+
+def test_pool_B1_decodes_all_fp8_codes(misa):
+    # With B = 1 pooling returns the de-quantised keys themselves, so this
+    # checks the hardware fp8 decode against the oracle's table for every code.
+    codes = np.arange(256, dtype=np.uint8)
+    codes[[0x7F, 0xFF]] = 0                               # NaN codes are not valid inputs
+    K = np.tile(codes.reshape(2, 128), (1, 1))[None]      # [1, 2, 128]
+    scale = np.array([[1.0, 0.37]], dtype=np.float32)
+    p = misa.Problem(1, 2, 1, 8, 1, 1, misa.FP8_E4M3, misa.BF16)
+    Kp = torch.empty((1, 2, 128), dtype=torch.float32, device="cuda")
+    misa.pool_keys(p, torch.from_numpy(K).cuda(), torch.from_numpy(scale).cuda(), Kp)
+    ref = O.dequantise(K[0], "e4m3", scale[0])
+    np.testing.assert_allclose(Kp.cpu().numpy()[0], ref, rtol=1e-6, atol=0)
+
+
+# --------------------------------------------------------------------- route
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("use_len", [False, True])
+def test_route_heads(misa, name, use_len):
+    wl = CASES[name]
+    inp = gen(name, ragged(wl) if use_len else None)
+    dv = misa.to_device(inp)
+    p = dv["problem"]
+    # pooled keys from the oracle (whole-cache pooling, fp32 storage)
+    Kp = np.zeros((wl.n_seq, p.M, wl.d), dtype=np.float32)
+    for s in range(wl.n_seq):
+        K, _, _, _ = oracle_view(inp, s, 0)
+        length = wl.L if inp["seq_len"] is None else int(inp["seq_len"][s])
+        ref = O.pool_keys(K, wl.B, length)
+        Kp[s, :ref.shape[0]] = ref
+    heads = torch.full((wl.n_seq, wl.n_q, wl.h), -5, dtype=torch.int32, device="cuda")
+    E = torch.empty((wl.n_seq, wl.n_q, wl.H), dtype=torch.float32, device="cuda")
+    ws = misa.alloc_workspace(p, misa.OP_ROUTE)
+    misa.route_heads(p, dv["Q"], dv["W"], torch.from_numpy(Kp).cuda(), dv["K"], dv["kscale"], heads, E, ws)
+    heads, E = heads.cpu().numpy(), E.cpu().numpy()
+    exact = 0
+    for s in range(wl.n_seq):
+        for t in range(wl.n_q):
+            K, q, w, n = oracle_view(inp, s, t)
+            ref_heads, ref_E = O.route_heads(q, w, K, wl.B, wl.h, n)
+            assert_scores_close(E[s, t], ref_E, f"E {name} {s},{t}")
+            exact += check_index_set(heads[s, t], ref_E, wl.h, f"heads {name} {s},{t}")
+    assert exact >= 0.9 * wl.n_seq * wl.n_q          # legal flips inside the margin must be rare
+
+
+# --------------------------------------------------------------------- score
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("use_len", [False, True])
+def test_score_tokens(misa, name, use_len):
+    wl = CASES[name]
+    inp = gen(name, ragged(wl) if use_len else None)
+    dv = misa.to_device(inp)
+    p = dv["problem"]
+    ref_heads = np.zeros((wl.n_seq, wl.n_q, wl.h), dtype=np.int32)
+    views = {}
+    for s in range(wl.n_seq):
+        for t in range(wl.n_q):
+            K, q, w, n = views[(s, t)] = oracle_view(inp, s, t)
+            ref_heads[s, t] = O.route_heads(q, w, K, wl.B, wl.h, n)[0]
+    S = torch.full((wl.n_seq, wl.n_q, wl.L), 3.0, dtype=torch.float32, device="cuda")
+    misa.score_tokens(p, dv["Q"], dv["W"], torch.from_numpy(ref_heads).cuda(), dv["K"], dv["kscale"], S)
+    got = S.cpu().numpy()
+    Sd = torch.empty_like(S)
+    misa.score_tokens(p, dv["Q"], dv["W"], None, dv["K"], dv["kscale"], Sd)      # all heads = dense DSA
+    got_dense = Sd.cpu().numpy()
+    for (s, t), (K, q, w, n) in views.items():
+        assert_scores_close(got[s, t, :n], O.score_tokens(q, w, ref_heads[s, t], K, n), f"score {name} {s},{t}")
+        assert np.all(np.isneginf(got[s, t, n:])), "invisible keys must score -inf"
+        assert_scores_close(got_dense[s, t, :n], O.dsa_scores(q, w, K, n), f"dense {name} {s},{t}")
+        assert np.all(np.isneginf(got_dense[s, t, n:]))
+
+
+def test_score_with_all_heads_listed_equals_dense(misa):
+    wl = CASES["bf16_decode"]
+    inp = gen("bf16_decode")
+    dv = misa.to_device(inp)
+    p = misa.Problem(wl.n_seq, wl.L, wl.n_q, wl.H, wl.B, wl.H, misa.BF16, misa.BF16)     # h = H
+    allh = torch.arange(wl.H, dtype=torch.int32, device="cuda").repeat(wl.n_seq, wl.n_q, 1).contiguous()
+    a = torch.empty((wl.n_seq, wl.n_q, wl.L), dtype=torch.float32, device="cuda")
+    b = torch.empty_like(a)
+    misa.score_tokens(p, dv["Q"], dv["W"], allh, dv["K"], dv["kscale"], a)
+    misa.score_tokens(p, dv["Q"], dv["W"], None, dv["K"], dv["kscale"], b)
+    assert torch.equal(a, b)
+
+
+# --------------------------------------------------------------------- top-k
+def _topk_case(misa, S, k, q_pos=None, seq_len=None):
+    n_seq, n_q, L = S.shape
+    p = misa.Problem(n_seq, L, n_q, 8, 16, 2, misa.F32, misa.F32,
+                     None if q_pos is None else torch.from_numpy(q_pos).cuda(),
+                     None if seq_len is None else torch.from_numpy(seq_len).cuda())
+    idx = torch.full((n_seq, n_q, k), -7, dtype=torch.int32, device="cuda")
+    val = torch.full((n_seq, n_q, k), 9.0, dtype=torch.float32, device="cuda")
+    misa.topk(p, torch.from_numpy(S).cuda(), k, idx, val)
+    idx, val = idx.cpu().numpy(), val.cpu().numpy()
+    for s in range(n_seq):
+        length = L if seq_len is None else int(np.clip(seq_len[s], 0, L))
+        for t in range(n_q):
+            n = length if q_pos is None else int(np.clip(int(q_pos[t]) + 1, 0, length))
+            ref = O.topk(S[s, t, :n].astype(np.float64), k) if n else np.zeros(0, np.int64)
+            ke = ref.shape[0]
+            np.testing.assert_array_equal(idx[s, t, :ke], ref, err_msg=f"row {s},{t}")
+            assert np.all(idx[s, t, ke:] == -1)
+            np.testing.assert_array_equal(val[s, t, :ke], S[s, t, ref])
+            assert np.all(np.isneginf(val[s, t, ke:]))
+
+
+def test_topk_random_rows_bit_exact(misa):
+    rng = np.random.default_rng(21)
+    S = rng.standard_normal((3, 1, 10007)).astype(np.float32)
+    for k in (1, 17, 2048, 10006, 10007, 12000):
+        _topk_case(misa, S, k)
+
+
+def test_topk_ties_zeros_and_constants(misa):
+    rng = np.random.default_rng(22)
+    S = (np.round(rng.standard_normal((2, 2, 5000)) * 3) / 3).astype(np.float32)     # heavy ties
+    S[0, 0, ::7] = 0.0; S[0, 0, 3::7] = -0.0                                        # signed zeros tie
+    S[1, 1, :] = 1.25                                                                # constant row
+    q_pos = np.array([4999, 2500], dtype=np.int32)
+    for k in (5, 256, 2048, 4999):
+        _topk_case(misa, S, k, q_pos=q_pos)
+
+
+def test_topk_short_and_empty_prefixes(misa):
+    rng = np.random.default_rng(23)
+    S = rng.standard_normal((4, 3, 300)).astype(np.float32)
+    q_pos = np.array([0, 5, 299], dtype=np.int32)
+    seq_len = np.array([300, 0, 4, 150], dtype=np.int32)
+    _topk_case(misa, S, 64, q_pos=q_pos, seq_len=seq_len)
+
+
+def test_topk_negative_and_extreme_values(misa):
+    rng = np.random.default_rng(24)
+    S = (rng.standard_normal((1, 2, 4096)) * 1e3).astype(np.float32)
+    S[0, 0, :100] = -np.inf
+    S[0, 1, 5] = 3e38; S[0, 1, 6] = -3e38; S[0, 1, 7] = 1e-44       # denormal
+    q_pos = np.array([4095, 4095], dtype=np.int32)
+    for k in (10, 4000, 4096):
+        _topk_case(misa, S, k, q_pos=q_pos)
+
+
+# --------------------------------------------------------------------- re-rank
+@pytest.mark.parametrize("name", ["fp8_prefill", "bf16_decode", "f32_prefill"])
+def test_rerank(misa, name):
+    wl = CASES[name]
+    inp = gen(name)
+    dv = misa.to_device(inp)
+    p = dv["problem"]
+    kc, k = 512, 96
+    cand = np.full((wl.n_seq, wl.n_q, kc), -1, dtype=np.int32)
+    views = {}
+    for s in range(wl.n_seq):
+        for t in range(wl.n_q):
+            K, q, w, n = views[(s, t)] = oracle_view(inp, s, t)
+            c = O.misa(q, w, K, wl.B, wl.h, kc, n)["tokens"]
+            cand[s, t, :c.shape[0]] = c
+    cand[0, 0, 3] = -1                      # a hole in the middle and an invisible index are skipped
+    cand[0, 0, kc - 1] = wl.L + 5
+    idx = torch.empty((wl.n_seq, wl.n_q, k), dtype=torch.int32, device="cuda")
+    val = torch.empty((wl.n_seq, wl.n_q, k), dtype=torch.float32, device="cuda")
+    ws = misa.alloc_workspace(p, misa.OP_RERANK, kc)
+    misa.rerank(p, dv["Q"], dv["W"], dv["K"], dv["kscale"], torch.from_numpy(cand).cuda(), kc, k, idx, val, ws)
+    idx, val = idx.cpu().numpy(), val.cpu().numpy()
+    for (s, t), (K, q, w, n) in views.items():
+        dense = O.dsa_scores(q, w, K, n)
+        valid = np.array(sorted(c for c in cand[s, t] if 0 <= c < n), dtype=np.int64)
+        ke = min(k, valid.shape[0])
+        got = idx[s, t]
+        assert np.all(got[ke:] == -1) and np.all(np.diff(got[:ke]) > 0)
+        assert set(got[:ke].tolist()) <= set(valid.tolist())
+        # positions of the chosen tokens inside the candidate list obey the margin rule
+        pos = np.searchsorted(valid, got[:ke])
+        padded = np.concatenate([pos, np.full(k - ke, -1, dtype=pos.dtype)])
+        check_index_set(padded, dense[valid], k, f"rerank {name} {s},{t}")
+        assert_scores_close(val[s, t, :ke], dense[got[:ke]], f"rerank values {name} {s},{t}")
+        assert np.all(np.isneginf(val[s, t, ke:]))
+
+
+# --------------------------------------------------------------------- determinism
+def test_run_twice_bit_identical(misa):
+    wl = CASES["fp8_prefill"]
+    inp = gen("fp8_prefill")
+    dv = misa.to_device(inp)
+    outs = []
+    for _ in range(2):
+        ix = misa.Indexer(dv["problem"], wl.k, wl.k_cand, want_E=True, want_val=True)
+        ix.run(dv["K"], dv["kscale"], dv["Q"], dv["W"])
+        torch.cuda.synchronize()
+        outs.append([x.clone() for x in (ix.Kp, ix.heads, ix.E, ix.S, ix.idx1, ix.idx, ix.val)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)

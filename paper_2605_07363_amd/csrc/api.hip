@@ -79,6 +79,7 @@ misa_status hip_result(hipError_t e, const char* what) {
 size_t ws_bytes_for(const misa::Prob& pr, int op, int k) {
   switch (op) {
     case MISA_OP_ROUTE: return misa::route_ws_bytes(pr);
+    case MISA_OP_TOPK: return misa::topk_ws_bytes(pr, k);
     case MISA_OP_RERANK:
       return k >= 1 ? (size_t)pr.n_seq * pr.n_q * (size_t)k * sizeof(float) : 0;
     default: return 0;
@@ -144,14 +145,14 @@ misa_status misa_score_tokens(const misa_problem* p, const void* Q, const float*
 
 misa_status misa_topk(const misa_problem* p, const float* S, int32_t k, int32_t* idx, float* val,
                       void* ws, size_t ws_bytes, void* stream) {
-  (void)ws; (void)ws_bytes;
   misa::Prob pr;
   misa_status st = check_problem(p, &pr);
   if (st != MISA_OK) return st;
   if (!S || !idx) return fail(MISA_ERR_INVALID_ARG, "S or idx is NULL");
   if (k < 1) return fail(MISA_ERR_INVALID_ARG, "k must be >= 1 (got %d)", k);
   if (k > misa::kMaxTopK) return fail(MISA_ERR_UNSUPPORTED, "k must be <= 16384 (got %d)", k);
-  return hip_result(misa::launch_topk(pr, S, pr.L, k, nullptr, idx, val, (hipStream_t)stream),
+  if ((st = check_ws(ws_bytes_for(pr, MISA_OP_TOPK, k), ws, ws_bytes)) != MISA_OK) return st;
+  return hip_result(misa::launch_topk(pr, S, pr.L, k, nullptr, idx, val, ws, (hipStream_t)stream),
                     "misa_topk launch");
 }
 
@@ -173,7 +174,7 @@ misa_status misa_rerank(const misa_problem* p, const void* Q, const float* W, co
   hipError_t e = misa::launch_score(pr, p->k_dtype, p->q_dtype, Q, W, nullptr, K, kscale, cand, k_cand,
                                     dense, (hipStream_t)stream);
   if (e != hipSuccess) return hip_result(e, "misa_rerank score launch");
-  return hip_result(misa::launch_topk(pr, dense, k_cand, k, cand, idx, val, (hipStream_t)stream),
+  return hip_result(misa::launch_topk(pr, dense, k_cand, k, cand, idx, val, nullptr, (hipStream_t)stream),
                     "misa_rerank top-k launch");
 }
 

@@ -26,7 +26,8 @@ hipError_t launch_score(const Prob& p, int k_dtype, int q_dtype, const void* Q, 
 // row_len slots, never selects -inf slots and reports map[slot].
 constexpr int kMaxTopK = 16384;
 constexpr int kMaxRowLen = 524288;
+size_t topk_ws_bytes(const Prob& p, int k);
 hipError_t launch_topk(const Prob& p, const float* S, int row_len, int k, const int* map, int* idx,
-                       float* val, hipStream_t st);
+                       float* val, void* ws, hipStream_t st);
 
 }  // namespace misa

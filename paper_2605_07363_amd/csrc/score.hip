@@ -17,6 +17,8 @@
 // score_generic_kernel: plain fp32 FMA path for every other combination
 //   (fp32 inputs, candidate lists).  One thread per key or candidate; the
 //   gathered query heads sit in LDS and are read by broadcast.
+#include <cstdlib>
+
 #include "kernels.h"
 
 namespace misa {
@@ -90,13 +92,20 @@ __global__ __launch_bounds__(256) void score_generic_kernel(
 }
 
 // ------------------------------------------------------------------ streaming
-// Widen 4 packed fp8 codes to 4 bf16 (exact: 3 mantissa bits fit in 7).
+// Widen 4 packed fp8 codes to 4 bf16 (exact: 3 mantissa bits fit in 7; scale 1).
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 __device__ __forceinline__ void fp8x4_to_bf16x4(uint32_t w, uint32_t& lo, uint32_t& hi) {
-  const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(w, false);
-  const f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8(w, true);
-  // take the upper halves of the two floats: bf16 pair (first value in the low half)
-  lo = __builtin_amdgcn_perm(__float_as_uint(a[1]), __float_as_uint(a[0]), 0x07060302u);
-  hi = __builtin_amdgcn_perm(__float_as_uint(b[1]), __float_as_uint(b[0]), 0x07060302u);
+  union { bf16x2 v; uint32_t u; } a, b;
+  a.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);  // codes 0,1
+  b.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true);   // codes 2,3
+  lo = a.u;
+  hi = b.u;
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_nt(const uint4* p) {
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
 }
 
 union Frag {
@@ -105,14 +114,15 @@ union Frag {
   uint32_t w[4];
 };
 
-// NT = 16-row head tiles (heads <= 16 * NT).
-template <int KDT, int NT>
+// NT = 16-row head tiles (heads <= 16 * NT); NG = 64-key groups per register buffer.
+template <int KDT, int NT, int NG, bool NTL>
 __global__ __launch_bounds__(256) void score_stream_kernel(
     Prob p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
     float* __restrict__ S) {
   constexpr int ROW_BYTES = KDT == MISA_BF16 ? 256 : 128;
-  constexpr int LANE_BYTES = ROW_BYTES / 4;  // one quarter row per lane
+  constexpr int STEP = 64 * NG;       // keys a wavefront consumes per pipeline step
+  constexpr int WG_STEP = 4 * STEP;   // ... and the four wavefronts of a workgroup together
   const int t = blockIdx.y, seq = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 15, g = lane >> 4;
@@ -120,92 +130,138 @@ __global__ __launch_bounds__(256) void score_stream_kernel(
   const int hc = heads ? p.h : p.H;
   const size_t qrow = (size_t)seq * p.n_q + t;
 
-  // A operand: head rows.  Lane (c, g) holds, for k-step i, the 8 components
-  // 32 g + 8 i .. + 7 of head row c of each tile; the key fragments use the
-  // same component mapping, so the contraction runs over all 128.
-  Frag a[NT][4];
-  float wv[NT][4];
-#pragma unroll
-  for (int T = 0; T < NT; ++T) {
-    const int r = T * 16 + c;
-    int head = -1;
-    if (r < hc) head = heads ? heads[qrow * p.h + r] : r;
-    if (head >= 0 && head < p.H) {
-      const uint4* src = reinterpret_cast<const uint4*>(Q + (qrow * p.H + head) * kD + 32 * g);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) a[T][i].u = src[i];
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) a[T][i].u = make_uint4(0, 0, 0, 0);
-    }
-    // The accumulator of lane (c, g) holds head rows 4 g + j (j = 0..3) for key column c.
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int rr = T * 16 + 4 * g + j;
-      int hd = -1;
-      if (rr < hc) hd = heads ? heads[qrow * p.h + rr] : rr;
-      wv[T][j] = (hd >= 0 && hd < p.H) ? W[qrow * p.H + hd] : 0.f;
-    }
-  }
-
   const char* kbase = static_cast<const char*>(K) + (size_t)seq * p.L * ROW_BYTES;
   float* srow = S + qrow * p.L;
   const int k_begin = blockIdx.x * keys_per_wg;
   const int k_end = min(k_begin + keys_per_wg, p.L);
 
-  for (int kg = k_begin + wave * 64; kg < k_end; kg += 256) {
-    const int key = kg + lane;  // the key this lane finally owns
-    if (kg >= n) {              // whole group invisible
-      if (key < p.L) srow[key] = -INFINITY;
-      continue;
-    }
-    // Load four 16-key tiles (rows clamped into the visible prefix: n >= 1 here).
-    Frag b[4][4];
-#pragma unroll
-    for (int tt = 0; tt < 4; ++tt) {
-      const int row = min(kg + tt * 16 + c, n - 1);
-      const char* src = kbase + (size_t)row * ROW_BYTES + g * LANE_BYTES;
-      if (KDT == MISA_BF16) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) b[tt][i].u = reinterpret_cast<const uint4*>(src)[i];
-      } else {
-        const uint4 lo = reinterpret_cast<const uint4*>(src)[0];
-        const uint4 hi = reinterpret_cast<const uint4*>(src)[1];
-        const uint32_t w8[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          fp8x4_to_bf16x4(w8[2 * i], b[tt][i].w[0], b[tt][i].w[1]);
-          fp8x4_to_bf16x4(w8[2 * i + 1], b[tt][i].w[2], b[tt][i].w[3]);
-        }
-      }
-    }
-    float scale = 1.f;
-    if (KDT == MISA_FP8_E4M3) scale = kscale[(size_t)seq * p.L + min(key, n - 1)];
+  Frag a[NT][4];   // query operand and gates, filled after the first key loads are issued
+  float wv[NT][4];
 
-    float part[4];
+  // Raw 16-byte key chunks of NG 64-key groups: 4 tiles x (4 bf16 | 2 fp8) loads per lane each.
+  constexpr int NLD = KDT == MISA_BF16 ? 4 : 2;
+  struct Raw { uint4 v[NG][4][NLD]; float scale[NG]; };
+
+  auto issue_loads = [&](Raw& r, int kg0) {
 #pragma unroll
-    for (int tt = 0; tt < 4; ++tt) {
-      float s = 0.f;
+    for (int q = 0; q < NG; ++q) {
+      const int kg = kg0 + 64 * q;
+      if (kg >= k_end || kg >= n) continue;  // nothing visible in this group (n >= 1 otherwise)
 #pragma unroll
-      for (int T = 0; T < NT; ++T) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      for (int tt = 0; tt < 4; ++tt) {
+        const int row = min(kg + tt * 16 + c, n - 1);  // clamped into the visible prefix
+        const uint4* src = reinterpret_cast<const uint4*>(kbase + (size_t)row * ROW_BYTES) + g;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[T][i].v, b[tt][i].v, acc, 0, 0, 0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) s = fmaf(wv[T][j], fmaxf(acc[j], 0.f), s);
+        for (int i = 0; i < NLD; ++i)
+          r.v[q][tt][i] = NTL ? load_nt(src + 4 * i) : src[4 * i];
       }
-      part[tt] = s;
+      r.scale[q] = 1.f;
+      if (KDT == MISA_FP8_E4M3) r.scale[q] = kscale[(size_t)seq * p.L + min(kg + lane, n - 1)];
     }
-    // Sum over the four lane groups so that group g ends with tile g.
-    const bool up2 = (g & 2) != 0, up1 = (g & 1) != 0;
-    const float r0 = __shfl_xor(up2 ? part[0] : part[2], 32);
-    const float r1 = __shfl_xor(up2 ? part[1] : part[3], 32);
-    const float k0 = (up2 ? part[2] : part[0]) + r0;
-    const float k1 = (up2 ? part[3] : part[1]) + r1;
-    const float r2 = __shfl_xor(up1 ? k0 : k1, 16);
-    const float fin = (up1 ? k1 : k0) + r2;
-    if (key < p.L) srow[key] = key < n ? fin * scale : -INFINITY;
+  };
+
+  auto finish_groups = [&](const Raw& r, int kg0) {
+#pragma unroll
+    for (int q = 0; q < NG; ++q) {
+      const int kg = kg0 + 64 * q;
+      const int key = kg + lane;  // the key this lane finally owns
+      if (kg >= k_end) continue;
+      if (kg >= n) {              // whole group invisible
+        if (key < p.L) srow[key] = -INFINITY;
+        continue;
+      }
+      float part[4];
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        Frag b[4];
+        if (KDT == MISA_BF16) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) b[i].u = r.v[q][tt][i % NLD];
+        } else {
+          const uint4 lo = r.v[q][tt][0], hi = r.v[q][tt][NLD - 1];
+          const uint32_t w8[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            fp8x4_to_bf16x4(w8[2 * i], b[i].w[0], b[i].w[1]);
+            fp8x4_to_bf16x4(w8[2 * i + 1], b[i].w[2], b[i].w[3]);
+          }
+        }
+        float s = 0.f;
+#pragma unroll
+        for (int T = 0; T < NT; ++T) {
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[T][i].v, b[i].v, acc, 0, 0, 0);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) s = fmaf(wv[T][j], fmaxf(acc[j], 0.f), s);
+        }
+        part[tt] = s;
+      }
+      // Sum over the four lane groups so that group g ends with tile g.
+      const bool up2 = (g & 2) != 0, up1 = (g & 1) != 0;
+      const float r0 = __shfl_xor(up2 ? part[0] : part[2], 32);
+      const float r1 = __shfl_xor(up2 ? part[1] : part[3], 32);
+      const float k0 = (up2 ? part[2] : part[0]) + r0;
+      const float k1 = (up2 ? part[3] : part[1]) + r1;
+      const float r2 = __shfl_xor(up1 ? k0 : k1, 16);
+      const float fin = (up1 ? k1 : k0) + r2;
+      if (key < p.L) srow[key] = key < n ? fin * r.scale[q] : -INFINITY;
+    }
+  };
+
+  // Software pipeline with two register buffers: the loads of the next step
+  // are all in flight before the current one is consumed.  The first key
+  // loads are issued before the query operand is gathered, so the dependent
+  // head-index -> gate / query loads overlap with them.
+  Raw bufA, bufB;
+  int kg = k_begin + wave * STEP;
+  issue_loads(bufA, kg);
+  __builtin_amdgcn_sched_barrier(0);
+
+  __shared__ int s_head[kMaxH];
+  __shared__ float s_gate[kMaxH];
+  if (threadIdx.x < kMaxH) {
+    const int r = threadIdx.x;
+    int head = -1;
+    if (r < hc) head = heads ? heads[qrow * p.h + r] : r;
+    const bool ok = head >= 0 && head < p.H;
+    s_head[r] = ok ? head : -1;
+    s_gate[r] = ok ? W[qrow * p.H + head] : 0.f;
+  }
+  __syncthreads();
+
+  // A operand: head rows.  The four lanes (c, g = 0..3) that share key column c
+  // read 64 contiguous bytes of a key row per load instruction (16-byte chunk
+  // 4 i + g for load i), so for bf16 keys k-step i covers components
+  // 8 (4 i + g) .. + 7, and for fp8 keys load i feeds k-steps 2 i and 2 i + 1
+  // with components 16 (4 i + g) + 8 j .. + 7.  The query fragments use the same
+  // component mapping, so the contraction still runs over all 128.
+#pragma unroll
+  for (int T = 0; T < NT; ++T) {
+    const int head = s_head[T * 16 + c];
+    const uint16_t* src = Q + (qrow * p.H + max(head, 0)) * kD;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int comp = KDT == MISA_BF16 ? 8 * (4 * i + g) : 16 * (4 * (i >> 1) + g) + 8 * (i & 1);
+      const uint4 v = *reinterpret_cast<const uint4*>(src + comp);
+      a[T][i].u = head >= 0 ? v : make_uint4(0, 0, 0, 0);
+    }
+    // The accumulator of lane (c, g) holds head rows 4 g + j (j = 0..3) for key column c.
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wv[T][j] = s_gate[T * 16 + 4 * g + j];
+  }
+
+  while (kg < k_end) {
+    issue_loads(bufB, kg + WG_STEP);
+    __builtin_amdgcn_sched_barrier(0);
+    finish_groups(bufA, kg);
+    kg += WG_STEP;
+    if (kg >= k_end) break;
+    issue_loads(bufA, kg + WG_STEP);
+    __builtin_amdgcn_sched_barrier(0);
+    finish_groups(bufB, kg);
+    kg += WG_STEP;
   }
 }
 
@@ -224,16 +280,22 @@ static hipError_t launch_stream(const Prob& p, const void* Q, const float* W, co
                                 const void* K, const float* kscale, float* S, hipStream_t st) {
   const int hc = heads ? p.h : p.H;
   const int nt = (hc + 15) / 16;
-  const int keys_per_wg = 1024;
+  static const int keys_per_wg = [] { const char* e = getenv("MISA_KEYS_PER_WG"); return e ? atoi(e) : 1024; }();
+  static const int variant = [] { const char* e = getenv("MISA_VARIANT"); return e ? atoi(e) : 0; }();
   const dim3 grid((p.L + keys_per_wg - 1) / keys_per_wg, p.n_q, p.n_seq);
   const uint16_t* q = static_cast<const uint16_t*>(Q);
-#define GO(NT) score_stream_kernel<KDT, NT><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S)
-  switch (nt) {
-    case 1: GO(1); break;
-    case 2: GO(2); break;
-    case 3: GO(3); break;
-    default: GO(4); break;
-  }
+#define GO(NT, NG, NTL) \
+  score_stream_kernel<KDT, NT, NG, NTL><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S)
+  if (nt == 1) {
+    switch (variant) {
+      case 1: GO(1, 2, false); break;
+      case 2: GO(1, 1, true); break;
+      case 3: GO(1, 2, true); break;
+      default: GO(1, 1, false); break;
+    }
+  } else if (nt == 2) GO(2, 1, false);
+  else if (nt == 3) GO(3, 1, false);
+  else GO(4, 1, false);
 #undef GO
   return hipGetLastError();
 }

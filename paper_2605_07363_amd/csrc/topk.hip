@@ -1,24 +1,36 @@
 // Stage 4: exact per-row top-k (Eq. dsa_topk, Eq. misa_topk, Eq. misa_candidate).
 //
-// One 1024-thread workgroup per score row.  The k-th largest value is found by
-// a most-significant-digit-first radix select (11 + 11 + 10 bits) on an
-// order-preserving integer image of the fp32 scores, with the digit histograms
-// in LDS.  Elements that are certainly selected (a more significant digit
-// above the threshold digit) are marked in an LDS bitmap as soon as that is
-// known; elements equal to the threshold value go to a second bitmap from
-// which the lowest-index ones are taken, which implements "ties to the lower
-// index" exactly.  The selected set is finally expanded from the bitmap in
-// index order with one block-wide prefix sum, so the output is ascending and
-// bit-reproducible without any sort.
+// The k-th largest value of a row is found by a most-significant-digit-first
+// radix select (11 + 11 + 10 bits) on an order-preserving integer image of the
+// fp32 scores.  Selected elements are marked in an LDS bitmap of the row and
+// the result is expanded from the bitmap in index order with one block-wide
+// prefix sum, so the output is ascending and bit-reproducible without a sort.
+//
+// Common case: after the first digit, the elements that share the threshold
+// digit ("boundary" elements) are few.  They are compacted into a small list
+// and every later digit, and the tie rule (equal values: lower index first),
+// is resolved on that list in LDS, so the row itself is read only twice.
+// If the boundary bin is larger than the list (heavily repeated values), the
+// kernel falls back to two more digit passes over the row and a bitmap of the
+// elements equal to the threshold value.
+//
+// Few long rows (decode): one workgroup per row would leave most of the chip
+// idle, so the two passes over the row are split over many workgroups
+// (topk_hist_kernel, topk_partition_kernel) that leave the histogram and the
+// compacted lists in the workspace; topk_kernel<true> then finishes each row
+// from those lists.
 #include "kernels.h"
 
 namespace misa {
 
 constexpr int kTopkThreads = 1024;
 constexpr int kBins = 2048;
+constexpr int kCap = 8192;          // boundary list capacity (entries)
+constexpr int kChunk = 8192;        // row elements per workgroup in the split passes
+constexpr int kPreHeader = kBins + 64;  // hist, then n_certain, n_boundary, padding
 
 // Finds the digit d (scanning from the top) with count(digit > d) < need <= count(digit >= d).
-// Thread i owns bins 2047-2i and 2046-2i.  Writes {d, need - count(digit > d)} to out[0..1].
+// Thread i owns bins 2047-2i and 2046-2i.  Writes {d, need - count(digit > d), hist[d]} to out.
 __device__ __forceinline__ void find_threshold_bin(const int* hist, int need, int* scan_scratch,
                                                    int* out) {
   const int tid = threadIdx.x;
@@ -27,41 +39,124 @@ __device__ __forceinline__ void find_threshold_bin(const int* hist, int need, in
   int total;
   const int above = block_exclusive_scan(ha + hb, scan_scratch, &total);
   if (above < need && need <= above + ha) {
-    out[0] = ba; out[1] = need - above;
+    out[0] = ba; out[1] = need - above; out[2] = ha;
   } else if (above + ha < need && need <= above + ha + hb) {
-    out[0] = bb; out[1] = need - above - ha;
+    out[0] = bb; out[1] = need - above - ha; out[2] = hb;
   }
   __syncthreads();
 }
 
+__device__ __forceinline__ void zero_hist(int* hist) {
+  for (int i = threadIdx.x; i < kBins; i += kTopkThreads) hist[i] = 0;
+  __syncthreads();
+}
+
+// Appends the flagged lanes' values to a list whose length counter lives at *counter
+// (LDS or global); one atomic per wavefront.  Returns the slot of this lane (or -1).
+__device__ __forceinline__ int wave_append(bool flag, int* counter) {
+  const unsigned long long mask = __ballot(flag);
+  if (mask == 0) return -1;
+  const int lane = threadIdx.x & 63;
+  const int leader = __ffsll((long long)mask) - 1;
+  int base = 0;
+  if (lane == leader) base = atomicAdd(counter, __popcll(mask));
+  base = __shfl(base, leader);
+  return flag ? base + __popcll(mask & ((1ull << lane) - 1ull)) : -1;
+}
+
+__device__ __forceinline__ int pre_stride(int k) { return (kPreHeader + k + 2 * kCap + 63) & ~63; }
+
+// ---------------------------------------------------------------- split pass 1
+__global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(Prob p, const float* __restrict__ S,
+                                                                 int k, int* __restrict__ pre) {
+  __shared__ int hist[kBins];
+  const int chunk = blockIdx.x, t = blockIdx.y, seq = blockIdx.z, tid = threadIdx.x;
+  const size_t row = (size_t)seq * p.n_q + t;
+  const int n = visible(p, seq, t);
+  const int lo = chunk * kChunk, hi = min(lo + kChunk, n);
+  if (lo >= hi) return;
+  zero_hist(hist);
+  const float* s = S + row * p.L;
+  for (int i = lo + tid; i < hi; i += kTopkThreads) atomicAdd(&hist[order_key(s[i]) >> 21], 1);
+  __syncthreads();
+  int* g = pre + row * pre_stride(k);
+  for (int i = tid; i < kBins; i += kTopkThreads)
+    if (hist[i]) atomicAdd(&g[i], hist[i]);
+}
+
+// ---------------------------------------------------------------- split pass 2
+__global__ __launch_bounds__(kTopkThreads) void topk_partition_kernel(Prob p,
+                                                                      const float* __restrict__ S,
+                                                                      int k, int* __restrict__ pre) {
+  __shared__ int scan_scratch[32];
+  __shared__ int thr[3];
+  const int chunk = blockIdx.x, t = blockIdx.y, seq = blockIdx.z, tid = threadIdx.x;
+  const size_t row = (size_t)seq * p.n_q + t;
+  const int n = visible(p, seq, t);
+  const int lo = chunk * kChunk, hi = min(lo + kChunk, n);
+  const int k_eff = min(k, n);
+  if (lo >= hi || k_eff == n) return;  // k_eff == n: everything is selected, nothing to partition
+  int* g = pre + row * pre_stride(k);
+  find_threshold_bin(g, k_eff, scan_scratch, thr);
+  const uint32_t d1 = thr[0];
+  const bool listed = thr[2] <= kCap;
+  int* certain = g + kPreHeader;
+  int* bkey = certain + k;
+  int* bidx = bkey + kCap;
+  const float* s = S + row * p.L;
+  for (int i0 = lo; i0 < hi; i0 += kTopkThreads) {  // whole wavefronts stay in the loop
+    const int i = i0 + tid;
+    uint32_t key = 0, a = 0;
+    const bool in = i < hi;
+    if (in) { key = order_key(s[i]); a = key >> 21; }
+    const int c = wave_append(in && a > d1, &g[kBins]);
+    if (c >= 0) certain[c] = i;
+    if (listed) {
+      const int b = wave_append(in && a == d1, &g[kBins + 1]);
+      if (b >= 0) { bkey[b] = (int)key; bidx[b] = i; }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- per-row kernel
+template <bool PRE>
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(Prob p, const float* __restrict__ S,
                                                             int row_len, int k,
                                                             const int* __restrict__ map,
                                                             int* __restrict__ idx,
-                                                            float* __restrict__ val) {
-  extern __shared__ uint32_t bitmaps[];  // sel[nwords_max] then eq[nwords_max]
+                                                            float* __restrict__ val,
+                                                            const int* __restrict__ pre) {
+  extern __shared__ uint32_t dyn[];  // sel bitmap, then eq bitmap OR boundary list (keys, idx)
   __shared__ int hist[kBins];
   __shared__ int scan_scratch[32];
-  __shared__ int thr[2];
+  __shared__ int thr[3];
+  __shared__ int list_len;
 
   const int t = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
   const size_t row = (size_t)seq * p.n_q + t;
   const float* s = S + row * row_len;
   const int n = map ? row_len : visible(p, seq, t);
   const int nwords_max = (row_len + 31) / 32;
-  uint32_t* sel = bitmaps;
-  uint32_t* eq = bitmaps + nwords_max;
+  uint32_t* sel = dyn;
+  uint32_t* eq = dyn + nwords_max;       // fallback path
+  uint32_t* lkey = dyn + nwords_max;     // list path (aliases eq)
+  int* lidx = reinterpret_cast<int*>(lkey + kCap);
   const int nwords = (n + 31) / 32;
   int* out_idx = idx + row * k;
   float* out_val = val ? val + row * k : nullptr;
+  const int* g = PRE ? pre + row * pre_stride(k) : nullptr;
 
-  for (int i = tid; i < nwords; i += kTopkThreads) { sel[i] = 0; eq[i] = 0; }
-  for (int i = tid; i < kBins; i += kTopkThreads) hist[i] = 0;
-  __syncthreads();
-
-  // ---- pass 1: histogram of the top 11 bits
-  for (int i = tid; i < n; i += kTopkThreads) atomicAdd(&hist[order_key(s[i]) >> 21], 1);
-  __syncthreads();
+  for (int i = tid; i < nwords; i += kTopkThreads) sel[i] = 0;
+  if (tid == 0) list_len = 0;
+  if (PRE) {
+    for (int i = tid; i < kBins; i += kTopkThreads) hist[i] = g[i];
+    __syncthreads();
+  } else {
+    zero_hist(hist);
+    // ---- pass 1: histogram of the top 11 bits
+    for (int i = tid; i < n; i += kTopkThreads) atomicAdd(&hist[order_key(s[i]) >> 21], 1);
+    __syncthreads();
+  }
 
   int selectable = n;
   if (map) {  // never select -inf slots (skipped candidates): they live in bins <= 3
@@ -84,71 +179,153 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(Prob p, const float*
     find_threshold_bin(hist, k_eff, scan_scratch, thr);
     const uint32_t d1 = thr[0];
     int need = thr[1];
+    const bool listed = thr[2] <= kCap;
     __syncthreads();
-    for (int i = tid; i < kBins; i += kTopkThreads) hist[i] = 0;
-    __syncthreads();
+    zero_hist(hist);
 
-    // ---- pass 2: mark digit1 > d1; histogram digit 2 within digit1 == d1
-    for (int i = tid; i < n; i += kTopkThreads) {
-      const uint32_t key = order_key(s[i]);
-      const uint32_t a = key >> 21;
-      if (a > d1) atomicOr(&sel[i >> 5], 1u << (i & 31));
-      else if (a == d1) atomicAdd(&hist[(key >> 10) & 0x7FF], 1);
-    }
-    __syncthreads();
-    find_threshold_bin(hist, need, scan_scratch, thr);
-    const uint32_t d2 = thr[0];
-    need = thr[1];
-    __syncthreads();
-    for (int i = tid; i < kBins; i += kTopkThreads) hist[i] = 0;
-    __syncthreads();
-
-    // ---- pass 3: within digit1 == d1: mark digit2 > d2; histogram digit 3 within == d2
-    const uint32_t pre22 = (d1 << 11) | d2;
-    for (int i = tid; i < n; i += kTopkThreads) {
-      const uint32_t key = order_key(s[i]);
-      if ((key >> 21) != d1) continue;
-      const uint32_t b = (key >> 10) & 0x7FF;
-      if (b > d2) atomicOr(&sel[i >> 5], 1u << (i & 31));
-      else if (b == d2) atomicAdd(&hist[key & 0x3FF], 1);
-    }
-    __syncthreads();
-    find_threshold_bin(hist, need, scan_scratch, thr);
-    const uint32_t d3 = thr[0];
-    need = thr[1];  // how many elements equal to the threshold value are taken
-    __syncthreads();
-    const uint32_t tkey = (pre22 << 10) | d3;
-
-    // ---- pass 4: within the 22-bit prefix: mark > threshold, collect == threshold
-    for (int i = tid; i < n; i += kTopkThreads) {
-      const uint32_t key = order_key(s[i]);
-      if ((key >> 10) != pre22) continue;
-      if (key > tkey) atomicOr(&sel[i >> 5], 1u << (i & 31));
-      else if (key == tkey) atomicOr(&eq[i >> 5], 1u << (i & 31));
-    }
-    __syncthreads();
-
-    // ---- take the `need` lowest-index elements among the ties
-    const int wpt = (nwords + kTopkThreads - 1) / kTopkThreads;
-    const int w_lo = min(tid * wpt, nwords), w_hi = min(w_lo + wpt, nwords);
-    int cnt = 0;
-    for (int w = w_lo; w < w_hi; ++w) cnt += __popc(eq[w]);
-    int total;
-    int before = block_exclusive_scan(cnt, scan_scratch, &total);
-    for (int w = w_lo; w < w_hi && before < need; ++w) {
-      uint32_t bits = eq[w];
-      const int c = __popc(bits);
-      int take = min(c, need - before);
-      before += c;
-      uint32_t kept = 0;
-      while (take-- > 0) {
-        const uint32_t low = bits & (0u - bits);
-        kept |= low;
-        bits ^= low;
+    if (listed) {
+      // ---- pass 2: mark digit1 > d1, compact digit1 == d1 into the LDS list
+      int len;
+      if (PRE) {
+        const int nc = g[kBins];
+        len = g[kBins + 1];
+        const int* certain = g + kPreHeader;
+        const int* bkey = certain + k;
+        const int* bidx = bkey + kCap;
+        for (int i = tid; i < nc; i += kTopkThreads) {
+          const int e = certain[i];
+          atomicOr(&sel[e >> 5], 1u << (e & 31));
+        }
+        for (int i = tid; i < len; i += kTopkThreads) { lkey[i] = (uint32_t)bkey[i]; lidx[i] = bidx[i]; }
+        __syncthreads();
+      } else {
+        const int n_up = (n + kTopkThreads - 1) / kTopkThreads * kTopkThreads;
+        for (int i = tid; i < n_up; i += kTopkThreads) {
+          uint32_t key = 0, a = 0;
+          const bool in = i < n;
+          if (in) { key = order_key(s[i]); a = key >> 21; }
+          if (in && a > d1) atomicOr(&sel[i >> 5], 1u << (i & 31));
+          const int b = wave_append(in && a == d1, &list_len);
+          if (b >= 0) { lkey[b] = key; lidx[b] = i; }
+        }
+        __syncthreads();
+        len = list_len;
       }
-      sel[w] |= kept;  // words are owned by one thread here
+      // ---- digits 2 and 3 on the list
+      for (int i = tid; i < len; i += kTopkThreads) atomicAdd(&hist[(lkey[i] >> 10) & 0x7FF], 1);
+      __syncthreads();
+      find_threshold_bin(hist, need, scan_scratch, thr);
+      const uint32_t d2 = thr[0];
+      need = thr[1];
+      __syncthreads();
+      zero_hist(hist);
+      for (int i = tid; i < len; i += kTopkThreads) {
+        const uint32_t key = lkey[i];
+        const uint32_t b = (key >> 10) & 0x7FF;
+        if (b > d2) atomicOr(&sel[lidx[i] >> 5], 1u << (lidx[i] & 31));
+        else if (b == d2) atomicAdd(&hist[key & 0x3FF], 1);
+      }
+      __syncthreads();
+      find_threshold_bin(hist, need, scan_scratch, thr);
+      const uint32_t low21 = (d2 << 10) | (uint32_t)thr[0];
+      need = thr[1];
+      const int ties = thr[2];
+      __syncthreads();
+      zero_hist(hist);
+      if (ties == need) {
+        for (int i = tid; i < len; i += kTopkThreads) {
+          const uint32_t l = lkey[i] & 0x1FFFFFu;
+          if ((l >> 10) == d2 && l >= low21) atomicOr(&sel[lidx[i] >> 5], 1u << (lidx[i] & 31));
+        }
+      } else {
+        // More ties than places: take the `need` lowest indices among them, by the
+        // same digit search on (high, low) halves of the index, inverted so that a
+        // lower index ranks higher.  Indices are distinct, so this is exact.
+        for (int i = tid; i < len; i += kTopkThreads) {
+          const uint32_t l = lkey[i] & 0x1FFFFFu;
+          if ((l >> 10) == d2 && l > low21) atomicOr(&sel[lidx[i] >> 5], 1u << (lidx[i] & 31));
+          else if (l == low21) atomicAdd(&hist[kBins - 1 - (lidx[i] >> 10)], 1);
+        }
+        __syncthreads();
+        find_threshold_bin(hist, need, scan_scratch, thr);
+        const int hi_digit = kBins - 1 - thr[0];
+        need = thr[1];
+        __syncthreads();
+        zero_hist(hist);
+        for (int i = tid; i < len; i += kTopkThreads) {
+          if ((lkey[i] & 0x1FFFFFu) != low21) continue;
+          const int e = lidx[i];
+          if ((e >> 10) < hi_digit) atomicOr(&sel[e >> 5], 1u << (e & 31));
+          else if ((e >> 10) == hi_digit) atomicAdd(&hist[kBins - 1 - (e & 0x3FF)], 1);
+        }
+        __syncthreads();
+        find_threshold_bin(hist, need, scan_scratch, thr);
+        const int lo_digit = kBins - 1 - thr[0];
+        for (int i = tid; i < len; i += kTopkThreads) {
+          if ((lkey[i] & 0x1FFFFFu) != low21) continue;
+          const int e = lidx[i];
+          if ((e >> 10) == hi_digit && (e & 0x3FF) <= lo_digit) atomicOr(&sel[e >> 5], 1u << (e & 31));
+        }
+      }
+      __syncthreads();
+    } else {
+      // ---- fallback: two more digit passes over the row, ties through a bitmap
+      for (int i = tid; i < nwords; i += kTopkThreads) eq[i] = 0;
+      __syncthreads();
+      for (int i = tid; i < n; i += kTopkThreads) {
+        const uint32_t key = order_key(s[i]);
+        const uint32_t a = key >> 21;
+        if (a > d1) atomicOr(&sel[i >> 5], 1u << (i & 31));
+        else if (a == d1) atomicAdd(&hist[(key >> 10) & 0x7FF], 1);
+      }
+      __syncthreads();
+      find_threshold_bin(hist, need, scan_scratch, thr);
+      const uint32_t d2 = thr[0];
+      need = thr[1];
+      __syncthreads();
+      zero_hist(hist);
+      const uint32_t pre22 = (d1 << 11) | d2;
+      for (int i = tid; i < n; i += kTopkThreads) {
+        const uint32_t key = order_key(s[i]);
+        if ((key >> 21) != d1) continue;
+        const uint32_t b = (key >> 10) & 0x7FF;
+        if (b > d2) atomicOr(&sel[i >> 5], 1u << (i & 31));
+        else if (b == d2) atomicAdd(&hist[key & 0x3FF], 1);
+      }
+      __syncthreads();
+      find_threshold_bin(hist, need, scan_scratch, thr);
+      const uint32_t tkey = (pre22 << 10) | (uint32_t)thr[0];
+      need = thr[1];  // how many elements equal to the threshold value are taken
+      __syncthreads();
+      for (int i = tid; i < n; i += kTopkThreads) {
+        const uint32_t key = order_key(s[i]);
+        if ((key >> 10) != pre22) continue;
+        if (key > tkey) atomicOr(&sel[i >> 5], 1u << (i & 31));
+        else if (key == tkey) atomicOr(&eq[i >> 5], 1u << (i & 31));
+      }
+      __syncthreads();
+      // take the `need` lowest-index elements among the ties
+      const int wpt = (nwords + kTopkThreads - 1) / kTopkThreads;
+      const int w_lo = min(tid * wpt, nwords), w_hi = min(w_lo + wpt, nwords);
+      int cnt = 0;
+      for (int w = w_lo; w < w_hi; ++w) cnt += __popc(eq[w]);
+      int total;
+      int before = block_exclusive_scan(cnt, scan_scratch, &total);
+      for (int w = w_lo; w < w_hi && before < need; ++w) {
+        uint32_t bits = eq[w];
+        const int c = __popc(bits);
+        int take = min(c, need - before);
+        before += c;
+        uint32_t kept = 0;
+        while (take-- > 0) {
+          const uint32_t low = bits & (0u - bits);
+          kept |= low;
+          bits ^= low;
+        }
+        sel[w] |= kept;  // words are owned by one thread here
+      }
+      __syncthreads();
     }
-    __syncthreads();
   }
 
   // ---- expand the bitmap in index order
@@ -172,18 +349,57 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(Prob p, const float*
   }
 }
 
-hipError_t launch_topk(const Prob& p, const float* S, int row_len, int k, const int* map, int* idx,
-                       float* val, hipStream_t st) {
-  const size_t lds = (size_t)2 * ((row_len + 31) / 32) * sizeof(uint32_t);
+__global__ void zero_ints_kernel(int* __restrict__ pre, int stride, int count) {
+  // clears the histogram and the two list counters of one row per blockIdx.y
+  int* g = pre + (size_t)blockIdx.y * stride;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < count; i += gridDim.x * blockDim.x) g[i] = 0;
+}
+
+// Rows are split over several workgroups when there are too few of them to fill the chip.
+static bool use_split(const Prob& p) {
+  return (long long)p.n_seq * p.n_q < 256 && p.L >= 4 * kChunk;
+}
+
+size_t topk_ws_bytes(const Prob& p, int k) {
+  if (!use_split(p) || k < 1) return 0;
+  const size_t stride = (size_t)((kPreHeader + k + 2 * kCap + 63) & ~63);
+  return (size_t)p.n_seq * p.n_q * stride * sizeof(int);
+}
+
+template <bool PRE>
+static hipError_t set_lds_limit(size_t lds) {
   static size_t attr_bytes = 48 * 1024;  // default dynamic LDS limit
   if (lds > attr_bytes) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(topk_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(topk_kernel<PRE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_bytes = lds;
   }
+  return hipSuccess;
+}
+
+hipError_t launch_topk(const Prob& p, const float* S, int row_len, int k, const int* map, int* idx,
+                       float* val, void* ws, hipStream_t st) {
+  const size_t nwords = (size_t)(row_len + 31) / 32;
+  const size_t second = nwords * 4 > (size_t)kCap * 8 ? nwords * 4 : (size_t)kCap * 8;
+  const size_t lds = nwords * 4 + second;
   const dim3 grid(p.n_q, p.n_seq);
-  topk_kernel<<<grid, kTopkThreads, lds, st>>>(p, S, row_len, k, map, idx, val);
+  if (!map && use_split(p)) {
+    int* pre = static_cast<int*>(ws);
+    const int stride = (kPreHeader + k + 2 * kCap + 63) & ~63;
+    const int rows = p.n_seq * p.n_q;
+    zero_ints_kernel<<<dim3(2, rows), 1024, 0, st>>>(pre, stride, kPreHeader);
+    const dim3 g2((p.L + kChunk - 1) / kChunk, p.n_q, p.n_seq);
+    topk_hist_kernel<<<g2, kTopkThreads, 0, st>>>(p, S, k, pre);
+    topk_partition_kernel<<<g2, kTopkThreads, 0, st>>>(p, S, k, pre);
+    hipError_t e = set_lds_limit<true>(lds);
+    if (e != hipSuccess) return e;
+    topk_kernel<true><<<grid, kTopkThreads, lds, st>>>(p, S, row_len, k, map, idx, val, pre);
+    return hipGetLastError();
+  }
+  hipError_t e = set_lds_limit<false>(lds);
+  if (e != hipSuccess) return e;
+  topk_kernel<false><<<grid, kTopkThreads, lds, st>>>(p, S, row_len, k, map, idx, val, nullptr);
   return hipGetLastError();
 }
 

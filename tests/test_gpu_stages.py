@@ -158,7 +158,7 @@ def _topk_case(misa, S, k, q_pos=None, seq_len=None):
                      None if seq_len is None else torch.from_numpy(seq_len).cuda())
     idx = torch.full((n_seq, n_q, k), -7, dtype=torch.int32, device="cuda")
     val = torch.full((n_seq, n_q, k), 9.0, dtype=torch.float32, device="cuda")
-    misa.topk(p, torch.from_numpy(S).cuda(), k, idx, val)
+    misa.topk(p, torch.from_numpy(S).cuda(), k, idx, val, misa.alloc_workspace(p, misa.OP_TOPK, k))
     idx, val = idx.cpu().numpy(), val.cpu().numpy()
     for s in range(n_seq):
         length = L if seq_len is None else int(np.clip(seq_len[s], 0, L))
@@ -205,6 +205,37 @@ def test_topk_negative_and_extreme_values(misa):
     q_pos = np.array([4095, 4095], dtype=np.int32)
     for k in (10, 4000, 4096):
         _topk_case(misa, S, k, q_pos=q_pos)
+
+
+def test_topk_long_rows_split_over_workgroups(misa):
+    # few long rows take the multi-workgroup path (histogram + partition + finish)
+    rng = np.random.default_rng(25)
+    S = rng.standard_normal((2, 2, 40000)).astype(np.float32)
+    q_pos = np.array([39999, 33333], dtype=np.int32)
+    for k in (1, 300, 2048, 8192, 16384):
+        _topk_case(misa, S, k, q_pos=q_pos)
+    _topk_case(misa, S, 2048, q_pos=q_pos, seq_len=np.array([40000, 35000], dtype=np.int32))
+    # decode rows whose visible prefix is not longer than k: everything is selected
+    _topk_case(misa, np.ascontiguousarray(S[:, :1]), 16384, seq_len=np.array([10000, 16385], dtype=np.int32))
+
+
+@pytest.mark.parametrize("shape", [(2, 1, 40000), (3, 300, 3000)])
+def test_topk_tie_paths(misa, shape):
+    rng = np.random.default_rng(26)
+    q_pos = None if shape[1] == 1 else np.full(shape[1], shape[2] - 1, dtype=np.int32)
+    # (a) few distinct values: the threshold value has far more copies than places (index digits decide)
+    S = rng.integers(0, 50, shape).astype(np.float32)
+    for k in (7, 1000, 2048):
+        _topk_case(misa, S, k, q_pos=q_pos)
+    # (b) constant rows and rows with one huge bin: more boundary elements than the list holds
+    S = np.full(shape, 0.75, dtype=np.float32)
+    S[0, 0, ::3] = 0.7500001
+    S[-1, -1, :] = 2.0
+    for k in (5, 2048):
+        _topk_case(misa, S, k, q_pos=q_pos)
+    # (c) values inside one binade only differing in low mantissa bits
+    S = (1.0 + rng.integers(0, 1 << 12, shape) * 2.0 ** -23).astype(np.float32)
+    _topk_case(misa, S, 1500, q_pos=q_pos)
 
 
 # --------------------------------------------------------------------- re-rank

@@ -265,6 +265,203 @@ __global__ __launch_bounds__(256) void score_stream_kernel(
   }
 }
 
+// ------------------------------------------------------------------ prefill
+// score_tile_kernel (bf16 queries, bf16 or fp8 keys, many queries per sequence):
+//   a dense contraction [queries x heads, 128] x [128, keys] on the matrix core
+//   (v_mfma_f32_32x32x16_bf16).  A workgroup owns a tile of queries and a range
+//   of keys.  Each wavefront keeps the gathered head rows of its own queries
+//   in registers for the whole key range (the query operand is stationary),
+//   while 64-key tiles stream through LDS, double buffered, widened to bf16
+//   once when they are staged and XOR-swizzled so that fragment reads are
+//   free of bank conflicts.  Head rows are placed so that all active heads of
+//   a query fall into accumulator registers of the same lane: a lane of the
+//   lower half-wave holds rows {0-3, 8-11, 16-19, 24-27} of a 32-row tile,
+//   the upper half the others, so ReLU, gate and the sum over heads need no
+//   cross-lane traffic, and 32 consecutive lanes store 32 consecutive keys.
+//   blockIdx.x is the key range and a multiple of 8 of them is launched, so
+//   workgroups that share a key range run on the same XCD and its L2.
+//
+// HS = head slots per query (h rounded up to 8, 16, 32 or 64).
+template <int HS>
+struct TileGeom {
+  static constexpr int RT = HS <= 32 ? 2 : 4;   // 32-row tiles per wavefront
+  static constexpr int QW = RT * 32 / HS;       // queries per wavefront
+  static constexpr int QWG = 4 * QW;            // queries per workgroup
+  // query (within the wavefront) and head slot of accumulator register r of
+  // row tile rt in half-wave hf
+  __device__ static __forceinline__ int query_of(int rt, int hf, int r) {
+    if (HS == 8) return rt * 4 + hf * 2 + (r >> 3);
+    if (HS == 16) return rt * 2 + hf;
+    return hf;
+  }
+  __device__ static __forceinline__ int slot_of(int rt, int r) {
+    if (HS == 8) return r & 7;
+    if (HS == 16) return r;
+    return rt * 16 + r;
+  }
+};
+
+constexpr int kKT = 64;  // keys per LDS tile
+
+template <int KDT, int HS>
+__global__ __launch_bounds__(256) void score_tile_kernel(
+    Prob p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
+    const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
+    float* __restrict__ S) {
+  using G = TileGeom<HS>;
+  constexpr int RT = G::RT, QW = G::QW, QWG = G::QWG;
+  constexpr int ROW_BYTES = KDT == MISA_BF16 ? 256 : 128;
+  constexpr int NLD = KDT == MISA_BF16 ? 4 : 2;  // 16-byte global loads per thread and tile
+  __shared__ uint4 ktile[2][kKT * 16];
+  __shared__ float kscl[2][kKT];
+  __shared__ int nvis[QWG];
+  __shared__ int s_head[QWG][HS];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, hf = lane >> 5;
+  const int seq = blockIdx.z;
+  const int q_base = blockIdx.y * QWG;
+  const int k_begin = blockIdx.x * keys_per_wg;
+  const int k_end = min(k_begin + keys_per_wg, p.L);
+  const int hc = heads ? p.h : p.H;
+
+  for (int i = tid; i < QWG; i += 256) nvis[i] = q_base + i < p.n_q ? visible(p, seq, q_base + i) : 0;
+  for (int i = tid; i < QWG * HS; i += 256) {
+    const int qi = i / HS, slot = i % HS, q = q_base + qi;
+    int head = -1;
+    if (q < p.n_q && slot < hc) head = heads ? heads[((size_t)seq * p.n_q + q) * p.h + slot] : slot;
+    s_head[qi][slot] = (head >= 0 && head < p.H) ? head : -1;
+  }
+  __syncthreads();
+  int n_max = 0;
+  for (int i = 0; i < QWG; ++i) n_max = max(n_max, nvis[i]);
+  const int k_stop = min(k_end, n_max);  // keys at or beyond this are invisible to every query here
+
+  // Stationary operand: row m = col of row tile rt belongs to half-wave (m >> 2) & 1 of the
+  // accumulator and to its register r = (m >> 3) * 4 + (m & 3).
+  Frag a[RT][8];
+  float gate[RT][16];
+  {
+    const int m = col, mhf = (m >> 2) & 1, mr = (m >> 3) * 4 + (m & 3);
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      const int qi = wave * QW + G::query_of(rt, mhf, mr), slot = G::slot_of(rt, mr);
+      const int head = s_head[qi][slot];
+      const uint16_t* src =
+          Q + (((size_t)seq * p.n_q + min(q_base + qi, p.n_q - 1)) * p.H + max(head, 0)) * kD + hf * 8;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const uint4 v = *reinterpret_cast<const uint4*>(src + ks * 16);
+        a[rt][ks].u = head >= 0 ? v : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int qj = wave * QW + G::query_of(rt, hf, r);
+        const int hd = s_head[qj][G::slot_of(rt, r)];
+        gate[rt][r] = hd >= 0 ? W[((size_t)seq * p.n_q + min(q_base + qj, p.n_q - 1)) * p.H + hd] : 0.f;
+      }
+    }
+  }
+
+  const char* kbase = static_cast<const char*>(K) + (size_t)seq * p.L * ROW_BYTES;
+  uint4 stage[NLD];
+  float stage_scale = 1.f;
+  auto load_tile = [&](int k0) {  // global -> registers, rows clamped into the cache
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int chunk = tid + 256 * i;
+      const int row = chunk / (ROW_BYTES / 16), c = chunk % (ROW_BYTES / 16);
+      stage[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)min(k0 + row, p.L - 1) * ROW_BYTES + c * 16);
+    }
+    if (KDT == MISA_FP8_E4M3 && tid < kKT) stage_scale = kscale[(size_t)seq * p.L + min(k0 + tid, p.L - 1)];
+  };
+  auto store_tile = [&](int buf) {  // registers -> LDS, bf16, chunk position XOR (row & 15)
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int chunk = tid + 256 * i;
+      const int row = chunk / (ROW_BYTES / 16), c = chunk % (ROW_BYTES / 16);
+      if (KDT == MISA_BF16) {
+        ktile[buf][row * 16 + (c ^ (row & 15))] = stage[i];
+      } else {
+        uint4 lo, hi;
+        fp8x4_to_bf16x4(stage[i].x, lo.x, lo.y);
+        fp8x4_to_bf16x4(stage[i].y, lo.z, lo.w);
+        fp8x4_to_bf16x4(stage[i].z, hi.x, hi.y);
+        fp8x4_to_bf16x4(stage[i].w, hi.z, hi.w);
+        ktile[buf][row * 16 + ((2 * c) ^ (row & 15))] = lo;
+        ktile[buf][row * 16 + ((2 * c + 1) ^ (row & 15))] = hi;
+      }
+    }
+    if (KDT == MISA_FP8_E4M3 && tid < kKT) kscl[buf][tid] = stage_scale;
+  };
+
+  // queries this lane reports, and their prefix lengths
+  constexpr int NQL = HS == 8 ? RT * 2 : (HS == 16 ? RT : 1);  // queries per lane
+  int qn[NQL];
+  float* qout[NQL];
+#pragma unroll
+  for (int j = 0; j < NQL; ++j) {
+    const int qi = wave * QW + (HS == 8 ? (j >> 1) * 4 + hf * 2 + (j & 1) : (HS == 16 ? j * 2 + hf : hf));
+    const bool ok = q_base + qi < p.n_q;
+    qn[j] = ok ? nvis[qi] : -1;   // -1: query does not exist, nothing is stored
+    qout[j] = S + ((size_t)seq * p.n_q + min(q_base + qi, p.n_q - 1)) * p.L;
+  }
+
+  int buf = 0;
+  if (k_begin < k_stop) {
+    load_tile(k_begin);
+    store_tile(0);
+  }
+  __syncthreads();
+  for (int k0 = k_begin; k0 < k_stop; k0 += kKT) {
+    const bool more = k0 + kKT < k_stop;
+    if (more) load_tile(k0 + kKT);
+#pragma unroll
+    for (int ct = 0; ct < kKT / 32; ++ct) {
+      f32x16 acc[RT];
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[rt][r] = 0.f;
+      const int row = ct * 32 + col;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        Frag b;
+        b.u = ktile[buf][row * 16 + ((ks * 2 + hf) ^ (row & 15))];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+          acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b.v, acc[rt], 0, 0, 0);
+      }
+      const int key = k0 + row;
+      float scale = 1.f;
+      if (KDT == MISA_FP8_E4M3) scale = kscl[buf][row];
+      float out[NQL];
+#pragma unroll
+      for (int j = 0; j < NQL; ++j) out[j] = 0.f;
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int j = HS == 8 ? rt * 2 + (r >> 3) : (HS == 16 ? rt : 0);
+          out[j] = fmaf(gate[rt][r], fmaxf(acc[rt][r], 0.f), out[j]);
+        }
+#pragma unroll
+      for (int j = 0; j < NQL; ++j)
+        if (key < k_end && qn[j] >= 0) qout[j][key] = key < qn[j] ? out[j] * scale : -INFINITY;
+    }
+    if (more) store_tile(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+  }
+  // keys of this range that no query of the tile can see
+  const int done = k_begin < k_stop ? k_begin + (k_stop - k_begin + kKT - 1) / kKT * kKT : k_begin;
+#pragma unroll
+  for (int j = 0; j < NQL; ++j) {
+    if (qn[j] < 0) continue;
+    for (int key = done + col; key < k_end; key += 32) qout[j][key] = -INFINITY;
+  }
+}
+
 template <int KDT, int QDT>
 static hipError_t launch_generic(const Prob& p, const void* Q, const float* W, const int* heads,
                                  const void* K, const float* kscale, const int* cand, int k_cand,
@@ -300,13 +497,46 @@ static hipError_t launch_stream(const Prob& p, const void* Q, const float* W, co
   return hipGetLastError();
 }
 
+template <int KDT>
+static hipError_t launch_tile(const Prob& p, const void* Q, const float* W, const int* heads,
+                              const void* K, const float* kscale, float* S, hipStream_t st) {
+  const int hc = heads ? p.h : p.H;
+  const int hs = hc <= 8 ? 8 : (hc <= 16 ? 16 : (hc <= 32 ? 32 : 64));
+  const int qwg = hs == 8 ? 32 : (hs == 16 ? 16 : 8);
+  const int q_tiles = (p.n_q + qwg - 1) / qwg;
+  // Key ranges: a multiple of 8 (one set per XCD), enough workgroups to fill
+  // the chip several times, at least 1024 keys each.
+  int splits = 8;
+  while (splits < 64 && (long long)splits * q_tiles * p.n_seq < 2048 && p.L / (splits * 2) >= 1024) splits *= 2;
+  int keys_per_wg = ((p.L + splits - 1) / splits + kKT - 1) / kKT * kKT;
+  const dim3 grid((p.L + keys_per_wg - 1) / keys_per_wg, q_tiles, p.n_seq);
+  const uint16_t* q = static_cast<const uint16_t*>(Q);
+#define GO(HS) score_tile_kernel<KDT, HS><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S)
+  switch (hs) {
+    case 8: GO(8); break;
+    case 16: GO(16); break;
+    case 32: GO(32); break;
+    default: GO(64); break;
+  }
+#undef GO
+  return hipGetLastError();
+}
+
+// Queries per sequence from which the tiled matrix-core kernel is used.
+constexpr int kTileMinQueries = 8;
+
 hipError_t launch_score(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,
                         const int* heads, const void* K, const float* kscale, const int* cand,
                         int k_cand, float* out, hipStream_t st) {
-  if (!cand && q_dtype == MISA_BF16 && k_dtype == MISA_BF16)
-    return launch_stream<MISA_BF16>(p, Q, W, heads, K, kscale, out, st);
-  if (!cand && q_dtype == MISA_BF16 && k_dtype == MISA_FP8_E4M3)
+  const bool mfma_ok = !cand && q_dtype == MISA_BF16 && k_dtype != MISA_F32;
+  if (mfma_ok && p.n_q >= kTileMinQueries) {
+    if (k_dtype == MISA_BF16) return launch_tile<MISA_BF16>(p, Q, W, heads, K, kscale, out, st);
+    return launch_tile<MISA_FP8_E4M3>(p, Q, W, heads, K, kscale, out, st);
+  }
+  if (mfma_ok) {
+    if (k_dtype == MISA_BF16) return launch_stream<MISA_BF16>(p, Q, W, heads, K, kscale, out, st);
     return launch_stream<MISA_FP8_E4M3>(p, Q, W, heads, K, kscale, out, st);
+  }
 #define GEN(KD, QD) return launch_generic<KD, QD>(p, Q, W, heads, K, kscale, cand, k_cand, out, st)
   if (q_dtype == MISA_F32) {
     if (k_dtype == MISA_F32) GEN(MISA_F32, MISA_F32);

@@ -462,6 +462,113 @@ __global__ __launch_bounds__(256) void score_tile_kernel(
   }
 }
 
+// ------------------------------------------------------------------ candidate re-scoring
+// score_gather_kernel (bf16 queries, bf16 or fp8 keys, candidate lists): the
+// fine stage of MISA-dagger scores k' gathered keys of one query with ALL heads
+// (Eq. dsa_score on the candidate set).  The query's H head rows are the
+// stationary operand (RT 32-row tiles in registers); each wavefront gathers 32
+// candidate keys per step straight from the (cache-resident) key cache into
+// MFMA fragments - a lane reads one contiguous half row - and the head sum is
+// in-lane over its accumulator registers plus one exchange between half-waves.
+template <int KDT, int RT>
+__global__ __launch_bounds__(256) void score_gather_kernel(
+    Prob p, int cand_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
+    const void* __restrict__ K, const float* __restrict__ kscale, const int* __restrict__ cand,
+    int k_cand, float* __restrict__ out) {
+  constexpr int ROW_BYTES = KDT == MISA_BF16 ? 256 : 128;
+  constexpr int NLD = KDT == MISA_BF16 ? 8 : 4;  // 16-byte loads per lane and key (half a row)
+  const int t = blockIdx.y, seq = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, hf = lane >> 5;
+  const int n = visible(p, seq, t);
+  const size_t qrow = (size_t)seq * p.n_q + t;
+  const int c_begin = blockIdx.x * cand_per_wg;
+  const int c_end = min(c_begin + cand_per_wg, k_cand);
+  const int* crow = cand + qrow * k_cand;
+  float* orow = out + qrow * k_cand;
+  const char* kbase = static_cast<const char*>(K) + (size_t)seq * p.L * ROW_BYTES;
+
+  // Row m of tile rt is head rt*32 + m; half-wave hf holds components 64 hf .. 64 hf + 63,
+  // k-step ks the eight from 64 hf + 8 ks (the key fragments use the same mapping).
+  Frag a[RT][8];
+  float gate[RT][16];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int head = rt * 32 + col;
+    const uint16_t* src = Q + (qrow * p.H + min(head, p.H - 1)) * kD + 64 * hf;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const uint4 v = *reinterpret_cast<const uint4*>(src + 8 * ks);
+      a[rt][ks].u = head < p.H ? v : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int hd = rt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+      gate[rt][r] = hd < p.H ? W[qrow * p.H + hd] : 0.f;
+    }
+  }
+
+  struct Raw { uint4 v[NLD]; float scale; int s; };
+  auto issue = [&](Raw& r, int c0) {
+    if (c0 >= c_end) return;
+    const int slot = c0 + col;
+    int s = slot < c_end ? crow[slot] : -1;
+    if (s >= n) s = -1;
+    r.s = s;
+    const int row = max(s, 0);
+    const uint4* src = reinterpret_cast<const uint4*>(kbase + (size_t)row * ROW_BYTES + hf * (ROW_BYTES / 2));
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) r.v[i] = src[i];
+    r.scale = 1.f;
+    if (KDT == MISA_FP8_E4M3) r.scale = kscale[(size_t)seq * p.L + row];
+  };
+  auto finish = [&](const Raw& r, int c0) {
+    if (c0 >= c_end) return;
+    f32x16 acc[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[rt][q] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      Frag b;
+      if (KDT == MISA_BF16) {
+        b.u = r.v[ks % NLD];
+      } else {
+        const uint4 w = r.v[(ks >> 1) % NLD];
+        fp8x4_to_bf16x4((ks & 1) ? w.z : w.x, b.w[0], b.w[1]);
+        fp8x4_to_bf16x4((ks & 1) ? w.w : w.y, b.w[2], b.w[3]);
+      }
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+        acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b.v, acc[rt], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) sum = fmaf(gate[rt][q], fmaxf(acc[rt][q], 0.f), sum);
+    sum += __shfl_xor(sum, 32);
+    const int slot = c0 + col;
+    if (hf == 0 && slot < c_end) orow[slot] = r.s >= 0 ? sum * r.scale : -INFINITY;
+  };
+
+  Raw bufA, bufB;
+  int c0 = c_begin + wave * 32;
+  issue(bufA, c0);
+  while (c0 < c_end) {
+    issue(bufB, c0 + 128);
+    __builtin_amdgcn_sched_barrier(0);
+    finish(bufA, c0);
+    c0 += 128;
+    if (c0 >= c_end) break;
+    issue(bufA, c0 + 128);
+    __builtin_amdgcn_sched_barrier(0);
+    finish(bufB, c0);
+    c0 += 128;
+  }
+}
+
 template <int KDT, int QDT>
 static hipError_t launch_generic(const Prob& p, const void* Q, const float* W, const int* heads,
                                  const void* K, const float* kscale, const int* cand, int k_cand,
@@ -525,9 +632,27 @@ static hipError_t launch_tile(const Prob& p, const void* Q, const float* W, cons
 // Queries per sequence from which the tiled matrix-core kernel is used.
 constexpr int kTileMinQueries = 8;
 
+template <int KDT>
+static hipError_t launch_gather(const Prob& p, const void* Q, const float* W, const void* K,
+                                const float* kscale, const int* cand, int k_cand, float* out,
+                                hipStream_t st) {
+  const int cand_per_wg = 2048;
+  const dim3 grid((k_cand + cand_per_wg - 1) / cand_per_wg, p.n_q, p.n_seq);
+  const uint16_t* q = static_cast<const uint16_t*>(Q);
+  if (p.H <= 32)
+    score_gather_kernel<KDT, 1><<<grid, 256, 0, st>>>(p, cand_per_wg, q, W, K, kscale, cand, k_cand, out);
+  else
+    score_gather_kernel<KDT, 2><<<grid, 256, 0, st>>>(p, cand_per_wg, q, W, K, kscale, cand, k_cand, out);
+  return hipGetLastError();
+}
+
 hipError_t launch_score(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,
                         const int* heads, const void* K, const float* kscale, const int* cand,
                         int k_cand, float* out, hipStream_t st) {
+  if (cand && !heads && q_dtype == MISA_BF16 && k_dtype != MISA_F32) {
+    if (k_dtype == MISA_BF16) return launch_gather<MISA_BF16>(p, Q, W, K, kscale, cand, k_cand, out, st);
+    return launch_gather<MISA_FP8_E4M3>(p, Q, W, K, kscale, cand, k_cand, out, st);
+  }
   const bool mfma_ok = !cand && q_dtype == MISA_BF16 && k_dtype != MISA_F32;
   if (mfma_ok && p.n_q >= kTileMinQueries) {
     if (k_dtype == MISA_BF16) return launch_tile<MISA_BF16>(p, Q, W, heads, K, kscale, out, st);

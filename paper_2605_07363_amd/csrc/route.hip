@@ -1,6 +1,14 @@
 // Stage 2: block-pooled head router (Eq. misa_route_score, Eq. misa_route).
 //
-// route_partial_kernel: lane = head.  Each lane keeps its query head in
+// route_tile_kernel (bf16 queries): the [queries x heads, 128] x [128, blocks]
+// product runs on the matrix core.  Query-head rows are the stationary operand
+// (registers); the fp32 pooled keys stream through LDS as two bf16 tiles, the
+// upper 16 bits of each value and the remainder, and both are multiplied, so
+// the products carry ~16 mantissa bits of the pooled key.  ReLU, the causal
+// block mask and the sum over blocks stay in accumulator lanes until the end
+// of the block range, when one wavefront reduction per row writes the partial
+// sum to the workspace.
+// route_partial_kernel (fp32 queries): lane = head.  Each lane keeps its query head in
 // registers; the pooled key of the block being visited is the same for the
 // whole wavefront, so it is fetched with wave-uniform (scalar) loads and every
 // FMA takes one scalar and one vector operand.  The four wavefronts of a
@@ -69,6 +77,158 @@ __global__ __launch_bounds__(256) void route_partial_kernel(Prob p, int splits,
     const float s = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
     part[(((size_t)seq * p.n_q + t) * splits + split) * kWave + lane] = s;
   }
+}
+
+constexpr int kRouteKT = 32;  // pooled blocks per LDS tile
+
+union RFrag {
+  bf16x8 v;
+  uint4 u;
+};
+
+// RG wavefronts of a workgroup own different 64-row groups; the other 4 / RG
+// "phases" take every (4 / RG)-th block tile of the same rows.
+template <int RG>
+__global__ __launch_bounds__(256) void route_tile_kernel(Prob p, int splits,
+                                                         const uint16_t* __restrict__ Q,
+                                                         const float* __restrict__ Kp,
+                                                         float* __restrict__ part) {
+  constexpr int CP = 4 / RG;
+  __shared__ uint2 tile[2][2][kRouteKT * 32];  // [buffer][hi | lo][block row * 32 + 8-byte slot]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, hf = lane >> 5;
+  const int split = blockIdx.x, seq = blockIdx.z;
+  const int rg = wave % RG, phase = wave / RG;
+  const int rows_per_seq = p.n_q * p.H;
+  const int row0 = (blockIdx.y * RG + rg) * 64;  // first (query, head) row of this wavefront
+  const int len = seq_length(p, seq);
+
+  const int per = (p.M + splits - 1) / splits;
+  const int b_lo = split * per, b_hi = min(b_lo + per, p.M);
+
+  // stationary operand and, per accumulator register, the number of pooled blocks its row may use
+  RFrag a[2][8];
+  int nb[2][16];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) {
+    const int row = row0 + rt * 32 + col;
+    const uint16_t* src = Q + ((size_t)seq * rows_per_seq + min(row, rows_per_seq - 1)) * kD + hf * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const uint4 v = *reinterpret_cast<const uint4*>(src + ks * 16);
+      a[rt][ks].u = row < rows_per_seq ? v : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int rr = row0 + rt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+      nb[rt][r] = rr < rows_per_seq ? pooled_blocks(visible(p, seq, rr / p.H), len, p.B) : 0;
+    }
+  }
+  int nb_max = 0;
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) nb_max = max(nb_max, nb[rt][r]);
+  // the block range this workgroup must visit: up to the largest count of any of its rows
+  __shared__ int s_stop;
+  if (tid == 0) s_stop = 0;
+  __syncthreads();
+  atomicMax(&s_stop, min(nb_max, b_hi));
+  __syncthreads();
+  const int b_stop = s_stop;
+
+  const float* kp_seq = Kp + (size_t)seq * p.M * kD;
+  float4 stage[4];
+  auto load_tile = [&](int b0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = tid + 256 * i;               // float4 index inside the 32 x 128 tile
+      const int row = e >> 5;
+      stage[i] = *reinterpret_cast<const float4*>(kp_seq + (size_t)min(b0 + row, p.M - 1) * kD + (e & 31) * 4);
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = tid + 256 * i;
+      const int row = e >> 5, c4 = e & 31;        // c4: group of 4 components
+      const float x[4] = {stage[i].x, stage[i].y, stage[i].z, stage[i].w};
+      uint32_t hi[4], lo[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t u = __float_as_uint(x[j]);
+        hi[j] = u & 0xFFFF0000u;                                   // upper 16 bits: exact bf16
+        lo[j] = __float_as_uint(x[j] - __uint_as_float(hi[j])) & 0xFFFF0000u;
+      }
+      // 16-byte chunk c4 / 2 of the row, XOR-swizzled by the row; 8-byte half c4 & 1
+      const int slot = row * 32 + (((c4 >> 1) ^ (row & 15)) << 1) + (c4 & 1);
+      tile[buf][0][slot] = make_uint2((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
+      tile[buf][1][slot] = make_uint2((lo[0] >> 16) | lo[1], (lo[2] >> 16) | lo[3]);
+    }
+  };
+
+  float sum[2][16];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum[rt][r] = 0.f;
+
+  int buf = 0;
+  if (b_lo < b_stop) {
+    load_tile(b_lo);
+    store_tile(0);
+  }
+  __syncthreads();
+  int it = 0;
+  for (int b0 = b_lo; b0 < b_stop; b0 += kRouteKT, ++it) {
+    const bool more = b0 + kRouteKT < b_stop;
+    if (more) load_tile(b0 + kRouteKT);
+    if (it % CP == phase) {
+      f32x16 acc[2];
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[rt][r] = 0.f;
+      const uint4* hi_t = reinterpret_cast<const uint4*>(tile[buf][0]);
+      const uint4* lo_t = reinterpret_cast<const uint4*>(tile[buf][1]);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        RFrag bh, bl;
+        const int idx = col * 16 + ((ks * 2 + hf) ^ (col & 15));
+        bh.u = hi_t[idx];
+        bl.u = lo_t[idx];
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+          acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, bh.v, acc[rt], 0, 0, 0);
+          acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, bl.v, acc[rt], 0, 0, 0);
+        }
+      }
+      const int b = b0 + col;
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          sum[rt][r] += (b < nb[rt][r] && b < b_hi) ? fmaxf(acc[rt][r], 0.f) : 0.f;
+    }
+    if (more) store_tile(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+  }
+
+  // sum over the 32 block columns of each half-wave, then one lane per row writes
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float v = sum[rt][r];
+#pragma unroll
+      for (int o = 16; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+      const int rr = row0 + rt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+      if (col == 0 && rr < rows_per_seq) {
+        const int t = rr / p.H, j = rr % p.H;
+        part[(((size_t)seq * p.n_q + t) * (splits * CP) + split * CP + phase) * kWave + j] = v;
+      }
+    }
 }
 
 template <int KDT, int QDT>
@@ -147,19 +307,26 @@ __global__ __launch_bounds__(128) void route_finalize_kernel(
   }
 }
 
+// Row groups (of 64 query-head rows) per workgroup of the tiled kernel.
+static int route_row_groups(const Prob& p) {
+  const long long groups = ((long long)p.n_q * p.H + 63) / 64;
+  return groups >= 4 ? 4 : (groups >= 2 ? 2 : 1);
+}
+
 int route_splits(const Prob& p) {
-  // Enough workgroups to cover the chip a few times, but at least 8 blocks per split.
-  const long long rows = (long long)p.n_seq * p.n_q;
-  long long s = (1024 + rows - 1) / rows;
-  const long long cap = (p.M + 7) / 8;
+  // Enough workgroups to cover the chip, but at least 4 block tiles (128 blocks) per split.
+  const long long wgs = (long long)p.n_seq * (((long long)p.n_q * p.H + 255) / 256);
+  long long s = (512 + wgs - 1) / wgs;
+  const long long cap = (p.M + 127) / 128;
   if (s > cap) s = cap;
-  if (s > 64) s = 64;
+  if (s > 16) s = 16;
   if (s < 1) s = 1;
   return (int)s;
 }
 
 size_t route_ws_bytes(const Prob& p) {
-  return (size_t)p.n_seq * p.n_q * route_splits(p) * kWave * sizeof(float);
+  // partial sums [n_seq, n_q, splits * 4, 64]: room for every column phase of the tiled kernel
+  return (size_t)p.n_seq * p.n_q * route_splits(p) * 4 * kWave * sizeof(float);
 }
 
 hipError_t launch_route(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,
@@ -167,16 +334,25 @@ hipError_t launch_route(const Prob& p, int k_dtype, int q_dtype, const void* Q, 
                         void* ws, hipStream_t st) {
   const int splits = route_splits(p);
   float* part = static_cast<float*>(ws);
-  const dim3 g1(splits, p.n_q, p.n_seq);
-  if (q_dtype == MISA_F32)
+  int total_splits = splits;
+  if (q_dtype == MISA_BF16) {
+    const int rg = route_row_groups(p);
+    total_splits = splits * (4 / rg);
+    const int rows = p.n_q * p.H;
+    const dim3 g1(splits, (rows + 64 * rg - 1) / (64 * rg), p.n_seq);
+    const uint16_t* q = static_cast<const uint16_t*>(Q);
+    if (rg == 4) route_tile_kernel<4><<<g1, 256, 0, st>>>(p, splits, q, Kp, part);
+    else if (rg == 2) route_tile_kernel<2><<<g1, 256, 0, st>>>(p, splits, q, Kp, part);
+    else route_tile_kernel<1><<<g1, 256, 0, st>>>(p, splits, q, Kp, part);
+  } else {
+    const dim3 g1(splits, p.n_q, p.n_seq);
     route_partial_kernel<MISA_F32><<<g1, 256, 0, st>>>(p, splits, Q, Kp, part);
-  else
-    route_partial_kernel<MISA_BF16><<<g1, 256, 0, st>>>(p, splits, Q, Kp, part);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const dim3 g2(p.n_q, p.n_seq);
 #define FIN(KD, QD) \
-  route_finalize_kernel<KD, QD><<<g2, 128, 0, st>>>(p, splits, Q, W, K, kscale, part, heads, E)
+  route_finalize_kernel<KD, QD><<<g2, 128, 0, st>>>(p, total_splits, Q, W, K, kscale, part, heads, E)
   if (q_dtype == MISA_F32) {
     if (k_dtype == MISA_F32) FIN(MISA_F32, MISA_F32);
     else if (k_dtype == MISA_BF16) FIN(MISA_BF16, MISA_F32);

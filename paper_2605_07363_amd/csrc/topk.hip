@@ -25,7 +25,7 @@ namespace misa {
 
 constexpr int kTopkThreads = 1024;
 constexpr int kBins = 2048;
-constexpr int kCap = 8192;          // boundary list capacity (entries)
+constexpr int kCap = 7000;          // boundary list capacity (entries); sized so two workgroups share a CU
 constexpr int kChunk = 8192;        // row elements per workgroup in the split passes
 constexpr int kPreHeader = kBins + 64;  // hist, then n_certain, n_boundary, padding
 
@@ -64,6 +64,28 @@ __device__ __forceinline__ int wave_append(bool flag, int* counter) {
   return flag ? base + __popcll(mask & ((1ull << lane) - 1ull)) : -1;
 }
 
+// Visits elements lo..hi-1 of a row with all threads of the block.  Eight
+// coalesced loads per thread are in flight before the first one is used.  f is
+// called by every thread of every wavefront in each round (in == false past
+// the end), so it may contain wavefront-wide operations.
+template <typename F>
+__device__ __forceinline__ void scan_row(const float* __restrict__ s, int lo, int hi, F f) {
+  constexpr int U = 8;
+  for (int base = lo; base < hi; base += kTopkThreads * U) {
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = base + u * kTopkThreads + (int)threadIdx.x;
+      v[u] = i < hi ? s[i] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = base + u * kTopkThreads + (int)threadIdx.x;
+      f(i, v[u], i < hi);
+    }
+  }
+}
+
 __device__ __forceinline__ int pre_stride(int k) { return (kPreHeader + k + 2 * kCap + 63) & ~63; }
 
 // ---------------------------------------------------------------- split pass 1
@@ -77,7 +99,9 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(Prob p, const f
   if (lo >= hi) return;
   zero_hist(hist);
   const float* s = S + row * p.L;
-  for (int i = lo + tid; i < hi; i += kTopkThreads) atomicAdd(&hist[order_key(s[i]) >> 21], 1);
+  scan_row(s, lo, hi, [&](int, float v, bool in) {
+    if (in) atomicAdd(&hist[order_key(v) >> 21], 1);
+  });
   __syncthreads();
   int* g = pre + row * pre_stride(k);
   for (int i = tid; i < kBins; i += kTopkThreads)
@@ -104,18 +128,15 @@ __global__ __launch_bounds__(kTopkThreads) void topk_partition_kernel(Prob p,
   int* bkey = certain + k;
   int* bidx = bkey + kCap;
   const float* s = S + row * p.L;
-  for (int i0 = lo; i0 < hi; i0 += kTopkThreads) {  // whole wavefronts stay in the loop
-    const int i = i0 + tid;
-    uint32_t key = 0, a = 0;
-    const bool in = i < hi;
-    if (in) { key = order_key(s[i]); a = key >> 21; }
+  scan_row(s, lo, hi, [&](int i, float v, bool in) {
+    const uint32_t key = order_key(v), a = key >> 21;
     const int c = wave_append(in && a > d1, &g[kBins]);
     if (c >= 0) certain[c] = i;
     if (listed) {
       const int b = wave_append(in && a == d1, &g[kBins + 1]);
       if (b >= 0) { bkey[b] = (int)key; bidx[b] = i; }
     }
-  }
+  });
 }
 
 // ---------------------------------------------------------------- per-row kernel
@@ -154,7 +175,9 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(Prob p, const float*
   } else {
     zero_hist(hist);
     // ---- pass 1: histogram of the top 11 bits
-    for (int i = tid; i < n; i += kTopkThreads) atomicAdd(&hist[order_key(s[i]) >> 21], 1);
+    scan_row(s, 0, n, [&](int, float v, bool in) {
+      if (in) atomicAdd(&hist[order_key(v) >> 21], 1);
+    });
     __syncthreads();
   }
 
@@ -199,15 +222,12 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(Prob p, const float*
         for (int i = tid; i < len; i += kTopkThreads) { lkey[i] = (uint32_t)bkey[i]; lidx[i] = bidx[i]; }
         __syncthreads();
       } else {
-        const int n_up = (n + kTopkThreads - 1) / kTopkThreads * kTopkThreads;
-        for (int i = tid; i < n_up; i += kTopkThreads) {
-          uint32_t key = 0, a = 0;
-          const bool in = i < n;
-          if (in) { key = order_key(s[i]); a = key >> 21; }
+        scan_row(s, 0, n, [&](int i, float v, bool in) {
+          const uint32_t key = order_key(v), a = key >> 21;
           if (in && a > d1) atomicOr(&sel[i >> 5], 1u << (i & 31));
           const int b = wave_append(in && a == d1, &list_len);
           if (b >= 0) { lkey[b] = key; lidx[b] = i; }
-        }
+        });
         __syncthreads();
         len = list_len;
       }
@@ -272,12 +292,12 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(Prob p, const float*
       // ---- fallback: two more digit passes over the row, ties through a bitmap
       for (int i = tid; i < nwords; i += kTopkThreads) eq[i] = 0;
       __syncthreads();
-      for (int i = tid; i < n; i += kTopkThreads) {
-        const uint32_t key = order_key(s[i]);
-        const uint32_t a = key >> 21;
+      scan_row(s, 0, n, [&](int i, float v, bool in) {
+        const uint32_t key = order_key(v), a = key >> 21;
+        if (!in) return;
         if (a > d1) atomicOr(&sel[i >> 5], 1u << (i & 31));
         else if (a == d1) atomicAdd(&hist[(key >> 10) & 0x7FF], 1);
-      }
+      });
       __syncthreads();
       find_threshold_bin(hist, need, scan_scratch, thr);
       const uint32_t d2 = thr[0];
@@ -285,24 +305,24 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(Prob p, const float*
       __syncthreads();
       zero_hist(hist);
       const uint32_t pre22 = (d1 << 11) | d2;
-      for (int i = tid; i < n; i += kTopkThreads) {
-        const uint32_t key = order_key(s[i]);
-        if ((key >> 21) != d1) continue;
+      scan_row(s, 0, n, [&](int i, float v, bool in) {
+        const uint32_t key = order_key(v);
+        if (!in || (key >> 21) != d1) return;
         const uint32_t b = (key >> 10) & 0x7FF;
         if (b > d2) atomicOr(&sel[i >> 5], 1u << (i & 31));
         else if (b == d2) atomicAdd(&hist[key & 0x3FF], 1);
-      }
+      });
       __syncthreads();
       find_threshold_bin(hist, need, scan_scratch, thr);
       const uint32_t tkey = (pre22 << 10) | (uint32_t)thr[0];
       need = thr[1];  // how many elements equal to the threshold value are taken
       __syncthreads();
-      for (int i = tid; i < n; i += kTopkThreads) {
-        const uint32_t key = order_key(s[i]);
-        if ((key >> 10) != pre22) continue;
+      scan_row(s, 0, n, [&](int i, float v, bool in) {
+        const uint32_t key = order_key(v);
+        if (!in || (key >> 10) != pre22) return;
         if (key > tkey) atomicOr(&sel[i >> 5], 1u << (i & 31));
         else if (key == tkey) atomicOr(&eq[i >> 5], 1u << (i & 31));
-      }
+      });
       __syncthreads();
       // take the `need` lowest-index elements among the ties
       const int wpt = (nwords + kTopkThreads - 1) / kTopkThreads;

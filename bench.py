@@ -77,6 +77,9 @@ def main() -> int:
     ap.add_argument("--workload", default="c3", choices=sorted(DESCRIPTIONS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate", type=int, default=3, help="key-cache copies rotated between steps (cold reads)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain device copies of the key cache (known size), as the reference "
+                         "reading for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the indexer shards by sequence / query rows "
@@ -113,6 +116,13 @@ def main() -> int:
             c()
             if ev is not None:
                 ev[j][1].record()
+
+    if args.copy_calibration:
+        scratch = torch.empty_like(dv["K"])
+        for _ in range(3):
+            scratch.copy_(dv["K"])          # reads and writes key_bytes each
+        torch.cuda.synchronize()
+        del scratch
 
     for i in range(args.warmup):
         step(i)

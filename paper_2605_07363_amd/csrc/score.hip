@@ -17,8 +17,6 @@
 // score_generic_kernel: plain fp32 FMA path for every other combination
 //   (fp32 inputs, candidate lists).  One thread per key or candidate; the
 //   gathered query heads sit in LDS and are read by broadcast.
-#include <cstdlib>
-
 #include "kernels.h"
 
 namespace misa {
@@ -102,121 +100,115 @@ __device__ __forceinline__ void fp8x4_to_bf16x4(uint32_t w, uint32_t& lo, uint32
   hi = b.u;
 }
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 load_nt(const uint4* p) {
-  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-  return make_uint4(v.x, v.y, v.z, v.w);
-}
-
 union Frag {
   bf16x8 v;
   uint4 u;
   uint32_t w[4];
 };
 
-// NT = 16-row head tiles (heads <= 16 * NT); NG = 64-key groups per register buffer.
-template <int KDT, int NT, int NG, bool NTL>
+// NT = 16-row head tiles (heads <= 16 * NT); a wavefront takes STEPS pipeline
+// steps of G 64-key groups each.
+template <int KDT, int NT, int STEPS, int G>
 __global__ __launch_bounds__(256) void score_stream_kernel(
-    Prob p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
+    Prob p, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
     float* __restrict__ S) {
   constexpr int ROW_BYTES = KDT == MISA_BF16 ? 256 : 128;
-  constexpr int STEP = 64 * NG;       // keys a wavefront consumes per pipeline step
-  constexpr int WG_STEP = 4 * STEP;   // ... and the four wavefronts of a workgroup together
+  constexpr int NLD = KDT == MISA_BF16 ? 4 : 2;  // 16-byte loads per lane and 16-key tile
+  constexpr int KPW = 256 * STEPS * G;           // keys per workgroup
   const int t = blockIdx.y, seq = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = lane & 15, g = lane >> 4;
   const int n = visible(p, seq, t);
   const int hc = heads ? p.h : p.H;
   const size_t qrow = (size_t)seq * p.n_q + t;
 
   const char* kbase = static_cast<const char*>(K) + (size_t)seq * p.L * ROW_BYTES;
+  const float* sbase = kscale + (size_t)seq * p.L;
   float* srow = S + qrow * p.L;
-  const int k_begin = blockIdx.x * keys_per_wg;
-  const int k_end = min(k_begin + keys_per_wg, p.L);
+  const int k_begin = blockIdx.x * KPW;
+  const int k_end = min(k_begin + KPW, p.L);
 
   Frag a[NT][4];   // query operand and gates, filled after the first key loads are issued
   float wv[NT][4];
 
-  // Raw 16-byte key chunks of NG 64-key groups: 4 tiles x (4 bf16 | 2 fp8) loads per lane each.
-  constexpr int NLD = KDT == MISA_BF16 ? 4 : 2;
-  struct Raw { uint4 v[NG][4][NLD]; float scale[NG]; };
+  // A workgroup whose whole key range is invisible only writes -inf.
+  if (k_begin >= n) {
+    for (int key = k_begin + threadIdx.x; key < k_end; key += 256) srow[key] = -INFINITY;
+    return;
+  }
 
-  auto issue_loads = [&](Raw& r, int kg0) {
+  // Raw 16-byte key chunks of one 64-key group: 4 tiles x NLD loads per lane.
+  // Loads are unconditional and branch-free (rows clamped into the cache), so
+  // that the number of loads in flight is known at every wait.
+  struct Raw { uint4 v[4][NLD]; float scale; };
+  auto issue_loads = [&](Raw& r, int kg) {
 #pragma unroll
-    for (int q = 0; q < NG; ++q) {
-      const int kg = kg0 + 64 * q;
-      if (kg >= k_end || kg >= n) continue;  // nothing visible in this group (n >= 1 otherwise)
+    for (int tt = 0; tt < 4; ++tt) {
+      const int row = min(kg + tt * 16 + c, p.L - 1);
+      const uint4* src = reinterpret_cast<const uint4*>(kbase + (size_t)row * ROW_BYTES) + g;
 #pragma unroll
-      for (int tt = 0; tt < 4; ++tt) {
-        const int row = min(kg + tt * 16 + c, n - 1);  // clamped into the visible prefix
-        const uint4* src = reinterpret_cast<const uint4*>(kbase + (size_t)row * ROW_BYTES) + g;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i)
-          r.v[q][tt][i] = NTL ? load_nt(src + 4 * i) : src[4 * i];
-      }
-      r.scale[q] = 1.f;
-      if (KDT == MISA_FP8_E4M3) r.scale[q] = kscale[(size_t)seq * p.L + min(kg + lane, n - 1)];
+      for (int i = 0; i < NLD; ++i) r.v[tt][i] = src[4 * i];
     }
+    r.scale = 1.f;
+    if (KDT == MISA_FP8_E4M3) r.scale = sbase[min(kg + lane, p.L - 1)];
   };
 
-  auto finish_groups = [&](const Raw& r, int kg0) {
-#pragma unroll
-    for (int q = 0; q < NG; ++q) {
-      const int kg = kg0 + 64 * q;
-      const int key = kg + lane;  // the key this lane finally owns
-      if (kg >= k_end) continue;
-      if (kg >= n) {              // whole group invisible
-        if (key < p.L) srow[key] = -INFINITY;
-        continue;
-      }
-      float part[4];
-#pragma unroll
-      for (int tt = 0; tt < 4; ++tt) {
-        Frag b[4];
-        if (KDT == MISA_BF16) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) b[i].u = r.v[q][tt][i % NLD];
-        } else {
-          const uint4 lo = r.v[q][tt][0], hi = r.v[q][tt][NLD - 1];
-          const uint32_t w8[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            fp8x4_to_bf16x4(w8[2 * i], b[i].w[0], b[i].w[1]);
-            fp8x4_to_bf16x4(w8[2 * i + 1], b[i].w[2], b[i].w[3]);
-          }
-        }
-        float s = 0.f;
-#pragma unroll
-        for (int T = 0; T < NT; ++T) {
-          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[T][i].v, b[i].v, acc, 0, 0, 0);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) s = fmaf(wv[T][j], fmaxf(acc[j], 0.f), s);
-        }
-        part[tt] = s;
-      }
-      // Sum over the four lane groups so that group g ends with tile g.
-      const bool up2 = (g & 2) != 0, up1 = (g & 1) != 0;
-      const float r0 = __shfl_xor(up2 ? part[0] : part[2], 32);
-      const float r1 = __shfl_xor(up2 ? part[1] : part[3], 32);
-      const float k0 = (up2 ? part[2] : part[0]) + r0;
-      const float k1 = (up2 ? part[3] : part[1]) + r1;
-      const float r2 = __shfl_xor(up1 ? k0 : k1, 16);
-      const float fin = (up1 ? k1 : k0) + r2;
-      if (key < p.L) srow[key] = key < n ? fin * r.scale[q] : -INFINITY;
+  auto finish_group = [&](const Raw& r, int kg) {
+    const int key = kg + lane;  // the key this lane finally owns
+    if (kg >= k_end) return;
+    if (kg >= n) {              // whole group invisible
+      if (key < p.L) srow[key] = -INFINITY;
+      return;
     }
+    float part[4];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+      Frag b[4];
+      if (KDT == MISA_BF16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) b[i].u = r.v[tt][i % NLD];
+      } else {
+        const uint4 lo = r.v[tt][0], hi = r.v[tt][NLD - 1];
+        const uint32_t w8[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          fp8x4_to_bf16x4(w8[2 * i], b[i].w[0], b[i].w[1]);
+          fp8x4_to_bf16x4(w8[2 * i + 1], b[i].w[2], b[i].w[3]);
+        }
+      }
+      float s = 0.f;
+#pragma unroll
+      for (int T = 0; T < NT; ++T) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[T][i].v, b[i].v, acc, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s = fmaf(wv[T][j], fmaxf(acc[j], 0.f), s);
+      }
+      part[tt] = s;
+    }
+    // Sum over the four lane groups so that group g ends with tile g.
+    const bool up2 = (g & 2) != 0, up1 = (g & 1) != 0;
+    const float r0 = __shfl_xor(up2 ? part[0] : part[2], 32);
+    const float r1 = __shfl_xor(up2 ? part[1] : part[3], 32);
+    const float k0 = (up2 ? part[2] : part[0]) + r0;
+    const float k1 = (up2 ? part[3] : part[1]) + r1;
+    const float r2 = __shfl_xor(up1 ? k0 : k1, 16);
+    const float fin = (up1 ? k1 : k0) + r2;
+    if (key < p.L) srow[key] = key < n ? fin * r.scale : -INFINITY;
   };
 
-  // Software pipeline with two register buffers: the loads of the next step
-  // are all in flight before the current one is consumed.  The first key
-  // loads are issued before the query operand is gathered, so the dependent
-  // head-index -> gate / query loads overlap with them.
-  Raw bufA, bufB;
-  int kg = k_begin + wave * STEP;
-  issue_loads(bufA, kg);
+  // Software pipeline with two register buffers, fully unrolled: the loads of
+  // the next group are all in flight before the current one is consumed.  The
+  // first key loads are issued before the query operand is gathered, so the
+  // dependent head-index -> gate / query loads overlap with them.
+  Raw buf[2][G];
+  const int kg0 = k_begin + wave * (64 * G);
+#pragma unroll
+  for (int q = 0; q < G; ++q) issue_loads(buf[0][q], kg0 + 64 * q);
   __builtin_amdgcn_sched_barrier(0);
 
   __shared__ int s_head[kMaxH];
@@ -252,16 +244,15 @@ __global__ __launch_bounds__(256) void score_stream_kernel(
     for (int j = 0; j < 4; ++j) wv[T][j] = s_gate[T * 16 + 4 * g + j];
   }
 
-  while (kg < k_end) {
-    issue_loads(bufB, kg + WG_STEP);
+#pragma unroll
+  for (int st = 0; st < STEPS; ++st) {
+    if (st + 1 < STEPS) {
+#pragma unroll
+      for (int q = 0; q < G; ++q) issue_loads(buf[(st + 1) & 1][q], kg0 + (st + 1) * 256 * G + 64 * q);
+    }
     __builtin_amdgcn_sched_barrier(0);
-    finish_groups(bufA, kg);
-    kg += WG_STEP;
-    if (kg >= k_end) break;
-    issue_loads(bufA, kg + WG_STEP);
-    __builtin_amdgcn_sched_barrier(0);
-    finish_groups(bufB, kg);
-    kg += WG_STEP;
+#pragma unroll
+    for (int q = 0; q < G; ++q) finish_group(buf[st & 1][q], kg0 + st * 256 * G + 64 * q);
   }
 }
 
@@ -584,22 +575,18 @@ static hipError_t launch_stream(const Prob& p, const void* Q, const float* W, co
                                 const void* K, const float* kscale, float* S, hipStream_t st) {
   const int hc = heads ? p.h : p.H;
   const int nt = (hc + 15) / 16;
-  static const int keys_per_wg = [] { const char* e = getenv("MISA_KEYS_PER_WG"); return e ? atoi(e) : 1024; }();
-  static const int variant = [] { const char* e = getenv("MISA_VARIANT"); return e ? atoi(e) : 0; }();
-  const dim3 grid((p.L + keys_per_wg - 1) / keys_per_wg, p.n_q, p.n_seq);
+  // 4 pipeline steps of one 64-key group per wavefront: 1024 keys per workgroup
+  // (measured best of 512 .. 4096 on MI355X for both bf16 and fp8 keys).
+  constexpr int STEPS = 4, G = 1, KPW = 256 * STEPS * G;
+  const dim3 grid((p.L + KPW - 1) / KPW, p.n_q, p.n_seq);
   const uint16_t* q = static_cast<const uint16_t*>(Q);
-#define GO(NT, NG, NTL) \
-  score_stream_kernel<KDT, NT, NG, NTL><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S)
-  if (nt == 1) {
-    switch (variant) {
-      case 1: GO(1, 2, false); break;
-      case 2: GO(1, 1, true); break;
-      case 3: GO(1, 2, true); break;
-      default: GO(1, 1, false); break;
-    }
-  } else if (nt == 2) GO(2, 1, false);
-  else if (nt == 3) GO(3, 1, false);
-  else GO(4, 1, false);
+#define GO(NT) score_stream_kernel<KDT, NT, STEPS, G><<<grid, 256, 0, st>>>(p, q, W, heads, K, kscale, S)
+  switch (nt) {
+    case 1: GO(1); break;
+    case 2: GO(2); break;
+    case 3: GO(3); break;
+    default: GO(4); break;
+  }
 #undef GO
   return hipGetLastError();
 }

@@ -22,6 +22,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
+# HBM bytes per launch of the score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
+# plain device copy of known size in the same run (profiles/score_stream_*_hbm_traffic.md).
+MEASURED_TRAFFIC_BYTES = {"c3": 571.1e6}
+
 DESCRIPTIONS = {
     "c0": "tiny decode: 1 seq x 1 query, L=4096, H=64, h=8, B=64, k=256, fp32",
     "c1": "batched decode: 64 seqs x 1 query, L=32768, H=64, h=8, B=64, k=2048, bf16 keys",
@@ -148,10 +152,11 @@ def main() -> int:
         algo = pairs * key_bytes_per_pair(wl)
         roof = {"kernel": "score_stream_kernel", "bound": "hbm", "achieved": algo / score_s / 1e9,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": algo / score_s / 1e9 / HBM_PEAK_GBS,
-                "traffic": None, "algorithmic_bytes": algo, "avg_launch_ms": stage_ms["score"]}
+                "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "algorithmic_bytes": algo,
+                "avg_launch_ms": stage_ms["score"]}
     else:
         flops = 2.0 * pairs * wl.h * wl.d
-        roof = {"kernel": "score (prefill)", "bound": "mfma", "achieved": flops / score_s / 1e12,
+        roof = {"kernel": "score_tile_kernel", "bound": "mfma", "achieved": flops / score_s / 1e12,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": flops / score_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                 "algorithmic_flops": flops, "avg_launch_ms": stage_ms["score"]}

@@ -85,6 +85,11 @@ struct Vec16<MISA_FP8_E4M3> {
   }
 };
 
+// ReLU as one integer max: non-negative floats have non-negative bit patterns,
+// negative ones (and -0.0) are negative integers, so max(bits, 0) is max(x, +0.0)
+// without the NaN-quieting instruction an IEEE fmaxf needs.
+__device__ __forceinline__ float relu(float x) { return __int_as_float(max(__float_as_int(x), 0)); }
+
 // Order-preserving image of a float: a > b (as floats, -0 == +0) <=> key(a) > key(b).
 __device__ __forceinline__ uint32_t order_key(float x) {
   uint32_t u = __float_as_uint(x);

@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256) void route_tile_kernel(Prob p, int splits,
       for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          sum[rt][r] += (b < nb[rt][r] && b < b_hi) ? fmaxf(acc[rt][r], 0.f) : 0.f;
+          sum[rt][r] += (b < nb[rt][r] && b < b_hi) ? relu(acc[rt][r]) : 0.f;
     }
     if (more) store_tile(buf ^ 1);
     __syncthreads();

@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256) void score_generic_kernel(
         }
       }
 #pragma unroll
-      for (int j = 0; j < 8; ++j) total = fmaf(wsm[hg + j], fmaxf(acc[j], 0.f), total);
+      for (int j = 0; j < 8; ++j) total = fmaf(wsm[hg + j], relu(acc[j]), total);
     }
     if (KDT == MISA_FP8_E4M3) total *= kscale[(size_t)seq * p.L + s];
     result = total;
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(256) void score_stream_kernel(
         for (int i = 0; i < 4; ++i)
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[T][i].v, b[i].v, acc, 0, 0, 0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) s = fmaf(wv[T][j], fmaxf(acc[j], 0.f), s);
+        for (int j = 0; j < 4; ++j) s = fmaf(wv[T][j], relu(acc[j]), s);
       }
       part[tt] = s;
     }
@@ -355,77 +355,101 @@ __global__ __launch_bounds__(256) void score_tile_kernel(
   }
 
   const char* kbase = static_cast<const char*>(K) + (size_t)seq * p.L * ROW_BYTES;
-  uint4 stage[NLD];
-  float stage_scale = 1.f;
-  auto load_tile = [&](int k0) {  // global -> registers, rows clamped into the cache
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int chunk = tid + 256 * i;
-      const int row = chunk / (ROW_BYTES / 16), c = chunk % (ROW_BYTES / 16);
-      stage[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)min(k0 + row, p.L - 1) * ROW_BYTES + c * 16);
+  // Staging registers of the next key tile (global -> registers -> LDS).  Thread
+  // tid moves the 16-byte chunks tid + 256 i of the tile.
+  constexpr int CPR = ROW_BYTES / 16;  // chunks per key row
+  uint4 st0 = make_uint4(0, 0, 0, 0), st1 = st0, st2 = st0, st3 = st0;
+  float st_scale = 1.f;
+#define MISA_TILE_LOAD(k0)                                                                        \
+  do {                                                                                            \
+    st0 = *reinterpret_cast<const uint4*>(kbase + (size_t)min((k0) + tid / CPR, p.L - 1) * ROW_BYTES + (tid % CPR) * 16); \
+    st1 = *reinterpret_cast<const uint4*>(kbase + (size_t)min((k0) + (tid + 256) / CPR, p.L - 1) * ROW_BYTES + (tid % CPR) * 16); \
+    if (NLD == 4) {                                                                               \
+      st2 = *reinterpret_cast<const uint4*>(kbase + (size_t)min((k0) + (tid + 512) / CPR, p.L - 1) * ROW_BYTES + (tid % CPR) * 16); \
+      st3 = *reinterpret_cast<const uint4*>(kbase + (size_t)min((k0) + (tid + 768) / CPR, p.L - 1) * ROW_BYTES + (tid % CPR) * 16); \
+    }                                                                                             \
+    if (KDT == MISA_FP8_E4M3 && tid < kKT) st_scale = kscale[(size_t)seq * p.L + min((k0) + tid, p.L - 1)]; \
+  } while (0)
+  auto put_chunk = [&](int b, int chunk, const uint4& v) {  // registers -> LDS, bf16, XOR (row & 15)
+    const int row = chunk / CPR, c = chunk % CPR;
+    if (KDT == MISA_BF16) {
+      ktile[b][row * 16 + (c ^ (row & 15))] = v;
+    } else {
+      uint4 lo, hi;
+      fp8x4_to_bf16x4(v.x, lo.x, lo.y);
+      fp8x4_to_bf16x4(v.y, lo.z, lo.w);
+      fp8x4_to_bf16x4(v.z, hi.x, hi.y);
+      fp8x4_to_bf16x4(v.w, hi.z, hi.w);
+      ktile[b][row * 16 + ((2 * c) ^ (row & 15))] = lo;
+      ktile[b][row * 16 + ((2 * c + 1) ^ (row & 15))] = hi;
     }
-    if (KDT == MISA_FP8_E4M3 && tid < kKT) stage_scale = kscale[(size_t)seq * p.L + min(k0 + tid, p.L - 1)];
   };
-  auto store_tile = [&](int buf) {  // registers -> LDS, bf16, chunk position XOR (row & 15)
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int chunk = tid + 256 * i;
-      const int row = chunk / (ROW_BYTES / 16), c = chunk % (ROW_BYTES / 16);
-      if (KDT == MISA_BF16) {
-        ktile[buf][row * 16 + (c ^ (row & 15))] = stage[i];
-      } else {
-        uint4 lo, hi;
-        fp8x4_to_bf16x4(stage[i].x, lo.x, lo.y);
-        fp8x4_to_bf16x4(stage[i].y, lo.z, lo.w);
-        fp8x4_to_bf16x4(stage[i].z, hi.x, hi.y);
-        fp8x4_to_bf16x4(stage[i].w, hi.z, hi.w);
-        ktile[buf][row * 16 + ((2 * c) ^ (row & 15))] = lo;
-        ktile[buf][row * 16 + ((2 * c + 1) ^ (row & 15))] = hi;
-      }
-    }
-    if (KDT == MISA_FP8_E4M3 && tid < kKT) kscl[buf][tid] = stage_scale;
-  };
+#define MISA_TILE_STORE(b)                                        \
+  do {                                                            \
+    put_chunk((b), tid, st0);                                     \
+    put_chunk((b), tid + 256, st1);                               \
+    if (NLD == 4) {                                               \
+      put_chunk((b), tid + 512, st2);                             \
+      put_chunk((b), tid + 768, st3);                             \
+    }                                                             \
+    if (KDT == MISA_FP8_E4M3 && tid < kKT) kscl[(b)][tid] = st_scale; \
+  } while (0)
 
-  // queries this lane reports, and their prefix lengths
+  // queries this lane reports: prefix lengths and 32-bit offsets of their score
+  // rows relative to the first row of the tile (uniform base + lane offset stores)
   constexpr int NQL = HS == 8 ? RT * 2 : (HS == 16 ? RT : 1);  // queries per lane
+  float* s_tile = S + ((size_t)seq * p.n_q + q_base) * p.L;
   int qn[NQL];
-  float* qout[NQL];
+  uint32_t qoff[NQL];
+  int n_min = 0x7FFFFFFF;
 #pragma unroll
   for (int j = 0; j < NQL; ++j) {
     const int qi = wave * QW + (HS == 8 ? (j >> 1) * 4 + hf * 2 + (j & 1) : (HS == 16 ? j * 2 + hf : hf));
     const bool ok = q_base + qi < p.n_q;
     qn[j] = ok ? nvis[qi] : -1;   // -1: query does not exist, nothing is stored
-    qout[j] = S + ((size_t)seq * p.n_q + min(q_base + qi, p.n_q - 1)) * p.L;
+    qoff[j] = (uint32_t)qi * (uint32_t)p.L;
   }
+  for (int i = 0; i < QWG; ++i) n_min = min(n_min, q_base + i < p.n_q ? nvis[i] : -1);
+  // tiles that end at or before plain_end are visible to every query of the
+  // workgroup, all of which exist: no masks are needed there
+  const int plain_end = min(n_min, k_end);
+
+  // LDS fragment positions of this lane (16-byte units): row col of column tile 0,
+  // chunk (2 ks + hf) XOR-swizzled by the row; the other tile is 32 rows further.
+  int frag[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) frag[ks] = col * 16 + ((ks * 2 + hf) ^ (col & 15));
 
   int buf = 0;
   if (k_begin < k_stop) {
-    load_tile(k_begin);
-    store_tile(0);
+    MISA_TILE_LOAD(k_begin);
+    MISA_TILE_STORE(0);
   }
   __syncthreads();
   for (int k0 = k_begin; k0 < k_stop; k0 += kKT) {
     const bool more = k0 + kKT < k_stop;
-    if (more) load_tile(k0 + kKT);
+    if (more) MISA_TILE_LOAD(k0 + kKT);
+    const bool plain = k0 + kKT <= plain_end;
+    const uint4* tile = ktile[buf];
 #pragma unroll
     for (int ct = 0; ct < kKT / 32; ++ct) {
       f32x16 acc[RT];
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[rt][r] = 0.f;
-      const int row = ct * 32 + col;
-#pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         Frag b;
-        b.u = ktile[buf][row * 16 + ((ks * 2 + hf) ^ (row & 15))];
+        b.u = tile[frag[ks] + ct * 512];
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-          acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b.v, acc[rt], 0, 0, 0);
+        for (int rt = 0; rt < RT; ++rt) {
+          if (ks == 0) {
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b.v, zero, 0, 0, 0);
+          } else {
+            acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b.v, acc[rt], 0, 0, 0);
+          }
+        }
       }
+      const int row = ct * 32 + col;
       const int key = k0 + row;
-      float scale = 1.f;
-      if (KDT == MISA_FP8_E4M3) scale = kscl[buf][row];
       float out[NQL];
 #pragma unroll
       for (int j = 0; j < NQL; ++j) out[j] = 0.f;
@@ -434,22 +458,34 @@ __global__ __launch_bounds__(256) void score_tile_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int j = HS == 8 ? rt * 2 + (r >> 3) : (HS == 16 ? rt : 0);
-          out[j] = fmaf(gate[rt][r], fmaxf(acc[rt][r], 0.f), out[j]);
+          out[j] = fmaf(gate[rt][r], relu(acc[rt][r]), out[j]);
         }
+      if (KDT == MISA_FP8_E4M3) {
+        const float scale = kscl[buf][row];
 #pragma unroll
-      for (int j = 0; j < NQL; ++j)
-        if (key < k_end && qn[j] >= 0) qout[j][key] = key < qn[j] ? out[j] * scale : -INFINITY;
+        for (int j = 0; j < NQL; ++j) out[j] *= scale;
+      }
+      if (plain) {
+#pragma unroll
+        for (int j = 0; j < NQL; ++j) s_tile[qoff[j] + (uint32_t)key] = out[j];
+      } else {
+#pragma unroll
+        for (int j = 0; j < NQL; ++j)
+          if (key < k_end && qn[j] >= 0) s_tile[qoff[j] + (uint32_t)key] = key < qn[j] ? out[j] : -INFINITY;
+      }
     }
-    if (more) store_tile(buf ^ 1);
+    if (more) MISA_TILE_STORE(buf ^ 1);
     __syncthreads();
     buf ^= 1;
   }
+#undef MISA_TILE_LOAD
+#undef MISA_TILE_STORE
   // keys of this range that no query of the tile can see
   const int done = k_begin < k_stop ? k_begin + (k_stop - k_begin + kKT - 1) / kKT * kKT : k_begin;
 #pragma unroll
   for (int j = 0; j < NQL; ++j) {
     if (qn[j] < 0) continue;
-    for (int key = done + col; key < k_end; key += 32) qout[j][key] = -INFINITY;
+    for (int key = done + col; key < k_end; key += 32) s_tile[qoff[j] + (uint32_t)key] = -INFINITY;
   }
 }
 
@@ -538,7 +574,7 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-      for (int q = 0; q < 16; ++q) sum = fmaf(gate[rt][q], fmaxf(acc[rt][q], 0.f), sum);
+      for (int q = 0; q < 16; ++q) sum = fmaf(gate[rt][q], relu(acc[rt][q]), sum);
     sum += __shfl_xor(sum, 32);
     const int slot = c0 + col;
     if (hf == 0 && slot < c_end) orow[slot] = r.s >= 0 ? sum * r.scale : -INFINITY;

@@ -178,6 +178,7 @@ __global__ __launch_bounds__(256) void route_tile_kernel(Prob p, int splits,
     load_tile(b_lo);
     store_tile(0);
   }
+  __builtin_amdgcn_s_waitcnt(0);  // prologue loads have landed; in-loop waits concern only loop loads
   __syncthreads();
   int it = 0;
   for (int b0 = b_lo; b0 < b_stop; b0 += kRouteKT, ++it) {

@@ -425,6 +425,9 @@ __global__ __launch_bounds__(256) void score_tile_kernel(
     MISA_TILE_LOAD(k_begin);
     MISA_TILE_STORE(0);
   }
+  // Every load of the prologue (query operand, gates) has landed before the loop
+  // starts, so the waits inside the loop only concern loads issued inside it.
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   for (int k0 = k_begin; k0 < k_stop; k0 += kKT) {
     const bool more = k0 + kKT < k_stop;
@@ -497,9 +500,11 @@ __global__ __launch_bounds__(256) void score_tile_kernel(
 // candidate keys per step straight from the (cache-resident) key cache into
 // MFMA fragments - a lane reads one contiguous half row - and the head sum is
 // in-lane over its accumulator registers plus one exchange between half-waves.
+constexpr int kGatherChunk = 2048;  // candidates per workgroup
+
 template <int KDT, int RT>
 __global__ __launch_bounds__(256) void score_gather_kernel(
-    Prob p, int cand_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
+    Prob p, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const void* __restrict__ K, const float* __restrict__ kscale, const int* __restrict__ cand,
     int k_cand, float* __restrict__ out) {
   constexpr int ROW_BYTES = KDT == MISA_BF16 ? 256 : 128;
@@ -509,11 +514,16 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
   const int col = lane & 31, hf = lane >> 5;
   const int n = visible(p, seq, t);
   const size_t qrow = (size_t)seq * p.n_q + t;
-  const int c_begin = blockIdx.x * cand_per_wg;
-  const int c_end = min(c_begin + cand_per_wg, k_cand);
+  const int c_begin = blockIdx.x * kGatherChunk;
+  const int c_end = min(c_begin + kGatherChunk, k_cand);
   const int* crow = cand + qrow * k_cand;
   float* orow = out + qrow * k_cand;
   const char* kbase = static_cast<const char*>(K) + (size_t)seq * p.L * ROW_BYTES;
+
+  // The candidate indices of this workgroup go through LDS, so that reading them
+  // in the loop does not wait on the key loads in flight.
+  __shared__ int s_cand[kGatherChunk];
+  for (int i = threadIdx.x; i < kGatherChunk; i += 256) s_cand[i] = c_begin + i < c_end ? crow[c_begin + i] : -1;
 
   // Row m of tile rt is head rt*32 + m; half-wave hf holds components 64 hf .. 64 hf + 63,
   // k-step ks the eight from 64 hf + 8 ks (the key fragments use the same mapping).
@@ -535,12 +545,13 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
     }
   }
 
+  // Loads are unconditional and branch-free (slot and row clamped), so the number
+  // of loads in flight is the same on every path and waits stay exact.
   struct Raw { uint4 v[NLD]; float scale; int s; };
   auto issue = [&](Raw& r, int c0) {
-    if (c0 >= c_end) return;
     const int slot = c0 + col;
-    int s = slot < c_end ? crow[slot] : -1;
-    if (s >= n) s = -1;
+    int s = s_cand[min(slot - c_begin, kGatherChunk - 1)];
+    if (slot >= c_end || s >= n) s = -1;
     r.s = s;
     const int row = max(s, 0);
     const uint4* src = reinterpret_cast<const uint4*>(kbase + (size_t)row * ROW_BYTES + hf * (ROW_BYTES / 2));
@@ -582,6 +593,8 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
 
   Raw bufA, bufB;
   int c0 = c_begin + wave * 32;
+  __builtin_amdgcn_s_waitcnt(0);  // the query operand has landed; in-loop waits concern only loop loads
+  __syncthreads();                // candidate indices are in LDS
   issue(bufA, c0);
   while (c0 < c_end) {
     issue(bufB, c0 + 128);
@@ -659,13 +672,12 @@ template <int KDT>
 static hipError_t launch_gather(const Prob& p, const void* Q, const float* W, const void* K,
                                 const float* kscale, const int* cand, int k_cand, float* out,
                                 hipStream_t st) {
-  const int cand_per_wg = 2048;
-  const dim3 grid((k_cand + cand_per_wg - 1) / cand_per_wg, p.n_q, p.n_seq);
+  const dim3 grid((k_cand + kGatherChunk - 1) / kGatherChunk, p.n_q, p.n_seq);
   const uint16_t* q = static_cast<const uint16_t*>(Q);
   if (p.H <= 32)
-    score_gather_kernel<KDT, 1><<<grid, 256, 0, st>>>(p, cand_per_wg, q, W, K, kscale, cand, k_cand, out);
+    score_gather_kernel<KDT, 1><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, out);
   else
-    score_gather_kernel<KDT, 2><<<grid, 256, 0, st>>>(p, cand_per_wg, q, W, K, kscale, cand, k_cand, out);
+    score_gather_kernel<KDT, 2><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, out);
   return hipGetLastError();
 }
 

@@ -33,7 +33,8 @@ __device__ __forceinline__ void load_query_head(const void* Q, size_t head_index
 // ceil(n/B) when the query sits at the end of the cache (the partial block in
 // Kp then holds exactly its tokens), else only the complete ones.
 __device__ __forceinline__ int pooled_blocks(int n, int len, int B) {
-  return n == len ? (int)(((long long)n + B - 1) / B) : n / B;
+  const int full = n / B;
+  return full + ((n == len && full * B != n) ? 1 : 0);
 }
 
 template <int QDT>
@@ -118,10 +119,19 @@ __global__ __launch_bounds__(256) void route_tile_kernel(Prob p, int splits,
       const uint4 v = *reinterpret_cast<const uint4*>(src + ks * 16);
       a[rt][ks].u = row < rows_per_seq ? v : make_uint4(0, 0, 0, 0);
     }
+    // the 16 rows of this lane belong to at most a few queries: the block count is
+    // recomputed only when the query changes
+    int t_prev = -1, nb_prev = 0;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int rr = row0 + rt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-      nb[rt][r] = rr < rows_per_seq ? pooled_blocks(visible(p, seq, rr / p.H), len, p.B) : 0;
+      int v = 0;
+      if (rr < rows_per_seq) {
+        const int t = rr / p.H;
+        if (t != t_prev) { nb_prev = pooled_blocks(visible(p, seq, t), len, p.B); t_prev = t; }
+        v = nb_prev;
+      }
+      nb[rt][r] = v;
     }
   }
   int nb_max = 0;

@@ -109,11 +109,19 @@ __global__ __launch_bounds__(kTopkThreads) void topk_hist_kernel(Prob p, const f
 }
 
 // ---------------------------------------------------------------- split pass 2
+// Each workgroup first compacts its chunk into LDS (certain indices from the
+// front, boundary entries from the back of one 8192-entry array: together they
+// never exceed the chunk), then reserves room in the row's global lists with
+// one atomic per list and copies the entries out with coalesced stores.
 __global__ __launch_bounds__(kTopkThreads) void topk_partition_kernel(Prob p,
                                                                       const float* __restrict__ S,
                                                                       int k, int* __restrict__ pre) {
   __shared__ int scan_scratch[32];
   __shared__ int thr[3];
+  __shared__ int cnt[2];    // certain, boundary entries of this chunk
+  __shared__ int base[2];   // their first slots in the row's lists
+  __shared__ int ent_idx[kChunk];
+  __shared__ uint32_t ent_key[kChunk];
   const int chunk = blockIdx.x, t = blockIdx.y, seq = blockIdx.z, tid = threadIdx.x;
   const size_t row = (size_t)seq * p.n_q + t;
   const int n = visible(p, seq, t);
@@ -121,6 +129,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_partition_kernel(Prob p,
   const int k_eff = min(k, n);
   if (lo >= hi || k_eff == n) return;  // k_eff == n: everything is selected, nothing to partition
   int* g = pre + row * pre_stride(k);
+  if (tid < 2) cnt[tid] = 0;
   find_threshold_bin(g, k_eff, scan_scratch, thr);
   const uint32_t d1 = thr[0];
   const bool listed = thr[2] <= kCap;
@@ -130,13 +139,23 @@ __global__ __launch_bounds__(kTopkThreads) void topk_partition_kernel(Prob p,
   const float* s = S + row * p.L;
   scan_row(s, lo, hi, [&](int i, float v, bool in) {
     const uint32_t key = order_key(v), a = key >> 21;
-    const int c = wave_append(in && a > d1, &g[kBins]);
-    if (c >= 0) certain[c] = i;
+    const int c = wave_append(in && a > d1, &cnt[0]);
+    if (c >= 0) ent_idx[c] = i;
     if (listed) {
-      const int b = wave_append(in && a == d1, &g[kBins + 1]);
-      if (b >= 0) { bkey[b] = (int)key; bidx[b] = i; }
+      const int b = wave_append(in && a == d1, &cnt[1]);
+      if (b >= 0) { ent_idx[kChunk - 1 - b] = i; ent_key[kChunk - 1 - b] = key; }
     }
   });
+  __syncthreads();
+  const int nc = cnt[0], nb = cnt[1];
+  if (tid == 0) base[0] = nc ? atomicAdd(&g[kBins], nc) : 0;
+  if (tid == 64) base[1] = nb ? atomicAdd(&g[kBins + 1], nb) : 0;
+  __syncthreads();
+  for (int i = tid; i < nc; i += kTopkThreads) certain[base[0] + i] = ent_idx[i];
+  for (int i = tid; i < nb; i += kTopkThreads) {
+    bkey[base[1] + i] = (int)ent_key[kChunk - 1 - i];
+    bidx[base[1] + i] = ent_idx[kChunk - 1 - i];
+  }
 }
 
 // ---------------------------------------------------------------- per-row kernel

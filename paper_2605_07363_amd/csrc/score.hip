@@ -17,6 +17,8 @@
 // score_generic_kernel: plain fp32 FMA path for every other combination
 //   (fp32 inputs, candidate lists).  One thread per key or candidate; the
 //   gathered query heads sit in LDS and are read by broadcast.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace misa {
@@ -420,66 +422,106 @@ __global__ __launch_bounds__(256) void score_tile_kernel(
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) frag[ks] = col * 16 + ((ks * 2 + hf) ^ (col & 15));
 
-  int buf = 0;
-  if (k_begin < k_stop) {
+  // One 32-key column tile: eight fragment reads, 8 x RT MFMAs.
+  auto mfma_tile = [&](f32x16 (&acc)[RT], const uint4* tile, int ct) {
+    Frag b[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) b[ks].u = tile[frag[ks] + ct * 512];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        if (ks == 0) {
+          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b[ks].v, zero, 0, 0, 0);
+        } else {
+          acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b[ks].v, acc[rt], 0, 0, 0);
+        }
+      }
+  };
+  // ReLU, gate, head sum and store of one finished column tile.  PLAIN: every
+  // query of the workgroup exists and sees the whole tile, so nothing is masked.
+  auto epilogue = [&](auto plain_tag, const f32x16 (&acc)[RT], int key, float scale) {
+    constexpr bool PLAIN = decltype(plain_tag)::value;
+    float out[NQL];
+#pragma unroll
+    for (int j = 0; j < NQL; ++j) out[j] = 0.f;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = HS == 8 ? rt * 2 + (r >> 3) : (HS == 16 ? rt : 0);
+        out[j] = fmaf(gate[rt][r], relu(acc[rt][r]), out[j]);
+      }
+    if (KDT == MISA_FP8_E4M3) {
+#pragma unroll
+      for (int j = 0; j < NQL; ++j) out[j] *= scale;
+    }
+    if (PLAIN) {
+#pragma unroll
+      for (int j = 0; j < NQL; ++j) s_tile[qoff[j] + (uint32_t)key] = out[j];
+    } else {
+#pragma unroll
+      for (int j = 0; j < NQL; ++j)
+        if (key < k_end && qn[j] >= 0) s_tile[qoff[j] + (uint32_t)key] = key < qn[j] ? out[j] : -INFINITY;
+    }
+  };
+  using Yes = std::true_type;
+  using No = std::false_type;
+  // Scheduling request for a block that holds the MFMAs of one column tile and the
+  // epilogue of the previous one: fragment reads first, then one MFMA followed by
+  // a share of the vector instructions, repeated, so that both pipes stay busy.
+  auto interleave = [&]() {
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);        // DS reads
+#pragma unroll
+    for (int i = 0; i < 8 * RT; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);     // ten VALU
+    }
+  };
+
+  // The column tiles of the key range form one stream; the MFMAs of a tile are
+  // issued together with the epilogue of the tile before it (two accumulator
+  // sets), so matrix and vector pipes overlap inside a wavefront.  Per 64-key
+  // LDS tile: [tile i, columns 32..63 | epilogue of columns 0..31], stage tile
+  // i+1 into the other LDS buffer, barrier, [tile i+1, columns 0..31 | epilogue
+  // of tile i, columns 32..63].
+  const int n_tiles = k_begin < k_stop ? (k_stop - k_begin + kKT - 1) / kKT : 0;
+  if (n_tiles > 0) {
     MISA_TILE_LOAD(k_begin);
     MISA_TILE_STORE(0);
-  }
-  // Every load of the prologue (query operand, gates) has landed before the loop
-  // starts, so the waits inside the loop only concern loads issued inside it.
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
-  for (int k0 = k_begin; k0 < k_stop; k0 += kKT) {
-    const bool more = k0 + kKT < k_stop;
-    if (more) MISA_TILE_LOAD(k0 + kKT);
-    const bool plain = k0 + kKT <= plain_end;
-    const uint4* tile = ktile[buf];
-#pragma unroll
-    for (int ct = 0; ct < kKT / 32; ++ct) {
-      f32x16 acc[RT];
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        Frag b;
-        b.u = tile[frag[ks] + ct * 512];
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-          if (ks == 0) {
-            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b.v, zero, 0, 0, 0);
-          } else {
-            acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b.v, acc[rt], 0, 0, 0);
-          }
-        }
-      }
-      const int row = ct * 32 + col;
-      const int key = k0 + row;
-      float out[NQL];
-#pragma unroll
-      for (int j = 0; j < NQL; ++j) out[j] = 0.f;
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = HS == 8 ? rt * 2 + (r >> 3) : (HS == 16 ? rt : 0);
-          out[j] = fmaf(gate[rt][r], relu(acc[rt][r]), out[j]);
-        }
-      if (KDT == MISA_FP8_E4M3) {
-        const float scale = kscl[buf][row];
-#pragma unroll
-        for (int j = 0; j < NQL; ++j) out[j] *= scale;
-      }
-      if (plain) {
-#pragma unroll
-        for (int j = 0; j < NQL; ++j) s_tile[qoff[j] + (uint32_t)key] = out[j];
-      } else {
-#pragma unroll
-        for (int j = 0; j < NQL; ++j)
-          if (key < k_end && qn[j] >= 0) s_tile[qoff[j] + (uint32_t)key] = key < qn[j] ? out[j] : -INFINITY;
-      }
-    }
-    if (more) MISA_TILE_STORE(buf ^ 1);
+    // Every load of the prologue (query operand, gates) has landed before the loop
+    // starts, so the waits inside the loop only concern loads issued inside it.
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    buf ^= 1;
+    if (n_tiles > 1) MISA_TILE_LOAD(k_begin + kKT);
+    f32x16 accA[RT], accB[RT];
+    float scaleA = 1.f, scaleB = 1.f;
+    mfma_tile(accA, ktile[0], 0);
+    if (KDT == MISA_FP8_E4M3) scaleA = kscl[0][col];
+    auto body = [&](auto tag, int i) {
+      const int buf = i & 1, k0 = k_begin + i * kKT;
+      const bool more = i + 1 < n_tiles;
+      mfma_tile(accB, ktile[buf], 1);
+      epilogue(tag, accA, k0 + col, scaleA);
+      interleave();
+      if (KDT == MISA_FP8_E4M3) scaleB = kscl[buf][32 + col];
+      if (more) MISA_TILE_STORE(buf ^ 1);
+      __syncthreads();
+      if (more) {
+        if (i + 2 < n_tiles) MISA_TILE_LOAD(k0 + 2 * kKT);
+        mfma_tile(accA, ktile[buf ^ 1], 0);
+        epilogue(tag, accB, k0 + 32 + col, scaleB);
+        interleave();
+        if (KDT == MISA_FP8_E4M3) scaleA = kscl[buf ^ 1][col];
+      } else {
+        epilogue(tag, accB, k0 + 32 + col, scaleB);
+      }
+    };
+    // leading tiles that need no masks, then the rest
+    const int n_plain = min(n_tiles, max(0, (plain_end - k_begin) / kKT));
+    for (int i = 0; i < n_plain; ++i) body(Yes{}, i);
+    for (int i = n_plain; i < n_tiles; ++i) body(No{}, i);
   }
 #undef MISA_TILE_LOAD
 #undef MISA_TILE_STORE

@@ -34,6 +34,11 @@ CASES = {
     "bf16_bigB": small("c1", n_seq=2, L=3000, B=5000, k=100),
     "bf16_B1": small("c1", n_seq=1, L=300, B=1, k=50, needles=4),
     "glm_dense_h": small("c3", n_seq=1, L=2000, h=32, B=128, k=100, needles=8),
+    # other head-slot widths of the prefill kernel (h = 16, 32, 3) and tiny head counts
+    "bf16_prefill_h16": small("c2", L=1500, n_q=21, h=16, B=64, k=100),
+    "fp8_prefill_h32": small("c4", L=1100, n_q=13, h=32, B=32, k=64, k_cand=256, needles=8),
+    "bf16_prefill_h3": small("c2", L=900, n_q=33, h=3, B=16, k=50),
+    "bf16_decode_H1": WL.scaled(WL.WORKLOADS["c1"], n_seq=2, L=700, H=1, h=1, B=8, k=20, needles=2),
 }
 
 
@@ -236,6 +241,27 @@ def test_topk_tie_paths(misa, shape):
     # (c) values inside one binade only differing in low mantissa bits
     S = (1.0 + rng.integers(0, 1 << 12, shape) * 2.0 ** -23).astype(np.float32)
     _topk_case(misa, S, 1500, q_pos=q_pos)
+
+
+def test_topk_longest_supported_rows(misa):
+    # L = 524288 (the documented limit) and k = 16384: split path (one row) and
+    # one-workgroup-per-row path (many rows; three of them checked)
+    rng = np.random.default_rng(27)
+    L = 524288
+    S = rng.standard_normal((1, 1, L)).astype(np.float32)
+    _topk_case(misa, S, 16384)
+    rows = 260
+    S = rng.standard_normal((1, rows, L)).astype(np.float32)
+    p = misa.Problem(1, L, rows, 8, 16, 2, misa.F32, misa.F32,
+                     torch.full((rows,), L - 1, dtype=torch.int32, device="cuda"))
+    k = 2048
+    idx = torch.empty((1, rows, k), dtype=torch.int32, device="cuda")
+    misa.topk(p, torch.from_numpy(S).cuda(), k, idx, None, misa.alloc_workspace(p, misa.OP_TOPK, k))
+    idx = idx.cpu().numpy()
+    for t in (0, 131, rows - 1):
+        ref = np.sort(np.argpartition(-S[0, t], k)[:k])      # no ties in random normals at this size
+        assert set(ref.tolist()) == set(O.topk(S[0, t, :].astype(np.float64), k).tolist()) if t == 0 else True
+        np.testing.assert_array_equal(idx[0, t], ref)
 
 
 # --------------------------------------------------------------------- re-rank

@@ -81,6 +81,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c3", choices=sorted(DESCRIPTIONS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate", type=int, default=3, help="key-cache copies rotated between steps (cold reads)")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch every kernel eagerly in the timed steps instead of replaying a HIP graph of the step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain device copies of the key cache (known size), as the reference "
                          "reading for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
@@ -132,7 +134,8 @@ def main() -> int:
         step(i)
     torch.cuda.synchronize()
 
-    # The library launches on torch's current stream, so torch events bracket its kernels.
+    # Per-stage durations: eager steps with events around every call.  The library
+    # launches on torch's current stream, so torch events bracket its kernels.
     events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                for _ in stage_names] for _ in range(args.steps)]
     torch.cuda.synchronize()
@@ -141,6 +144,33 @@ def main() -> int:
         step(args.warmup + i, events[i])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    eager_ms = dt / args.steps * 1e3
+
+    # Timed region proper: the same step (all calls, same buffers) captured once per
+    # key-cache copy into a HIP graph and replayed, which removes the launch gaps
+    # between the 5-10 short kernels of a step.  Every replay is checked against
+    # the eager result.
+    use_graph = not args.no_graph
+    if use_graph:
+        expect = ix.idx.clone()
+        graphs = []
+        for r in range(n_rot):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step(r)
+            graphs.append(g)
+        for r in range(n_rot):                      # untimed: first replays + correctness of each graph
+            ix.idx.fill_(-7)
+            graphs[r].replay()
+            torch.cuda.synchronize()
+            assert torch.equal(ix.idx, expect), "graph replay differs from the eager step"
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[(args.warmup + i) % n_rot].replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        assert torch.equal(ix.idx, expect), "graph replay differs from the eager step"
 
     ms_per_step = dt / args.steps * 1e3
     pairs = wl.pairs()
@@ -168,6 +198,8 @@ def main() -> int:
         "vs_baseline": None, "dtype": "f32" if wl.k_dtype == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {DESCRIPTIONS[wl.name]}", "pairs_per_step": pairs,
                    "key_cache_bytes": key_bytes, "key_buffers_rotated": n_rot},
+        "launch": "hip-graph replay of the whole step" if use_graph else "eager",
+        "eager_ms_per_step": eager_ms,
         "stage_ms": stage_ms,
         "score_stage_pairs_per_s": pairs / score_s,
         "roofline": roof,

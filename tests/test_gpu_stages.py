@@ -243,6 +243,33 @@ def test_topk_tie_paths(misa, shape):
     _topk_case(misa, S, 1500, q_pos=q_pos)
 
 
+def test_topk_sampled_single_read_path(misa):
+    # many long rows: the kernel brackets the threshold from a sample and reads the row
+    # once; rows built to defeat the sample must fall back and still be exact
+    rng = np.random.default_rng(28)
+    rows, L = 264, 40000
+    S = rng.standard_normal((1, rows, L)).astype(np.float32)
+    S[0, 1] = np.sort(S[0, 1])                                  # ascending
+    S[0, 2] = np.sort(S[0, 2])[::-1]                            # descending
+    S[0, 3] = rng.integers(0, 7, L).astype(np.float32)          # few distinct values
+    S[0, 4] = 0.5                                               # constant
+    S[0, 5] = -np.abs(S[0, 5]); S[0, 5].reshape(-1, 32)[8::16] = 5.0 + rng.random((L // 32 + 15 - 8) // 16 * 32).reshape(-1, 32)[: len(S[0, 5].reshape(-1, 32)[8::16])]
+    S[0, 6] = -np.abs(S[0, 6]); S[0, 6].reshape(-1, 32)[3::16] += 6.0   # large values only in lines the sample skips
+    S[0, 7, :20000] = -np.inf                                   # half the row at -inf
+    q_pos = np.full(rows, L - 1, dtype=np.int32); q_pos[9] = 33000; q_pos[10] = 32767
+    p = misa.Problem(1, L, rows, 8, 16, 2, misa.F32, misa.F32, torch.from_numpy(q_pos).cuda())
+    for k in (2048, 100, 9000):
+        idx = torch.empty((1, rows, k), dtype=torch.int32, device="cuda")
+        val = torch.empty((1, rows, k), dtype=torch.float32, device="cuda")
+        misa.topk(p, torch.from_numpy(S).cuda(), k, idx, val, misa.alloc_workspace(p, misa.OP_TOPK, k))
+        idx, val = idx.cpu().numpy(), val.cpu().numpy()
+        for t in list(range(12)) + [100, rows - 1]:
+            n = int(q_pos[t]) + 1
+            ref = O.topk(S[0, t, :n].astype(np.float64), k)
+            np.testing.assert_array_equal(idx[0, t, :ref.shape[0]], ref, err_msg=f"row {t} k {k}")
+            np.testing.assert_array_equal(val[0, t, :ref.shape[0]], S[0, t, ref])
+
+
 def test_topk_longest_supported_rows(misa):
     # L = 524288 (the documented limit) and k = 16384: split path (one row) and
     # one-workgroup-per-row path (many rows; three of them checked)

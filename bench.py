@@ -79,6 +79,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=sorted(DESCRIPTIONS))
+    ap.add_argument("--block", type=int, default=0, help="override the router block size B of the workload")
+    ap.add_argument("--active-heads", type=int, default=0, help="override the number of active heads h")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate", type=int, default=3, help="key-cache copies rotated between steps (cold reads)")
     ap.add_argument("--no-graph", action="store_true",
@@ -96,6 +98,9 @@ def main() -> int:
     from paper_2605_07363_amd import misa, workloads as WL
 
     wl = WL.WORKLOADS[args.workload]
+    override = {k: v for k, v in (("B", args.block), ("h", args.active_heads)) if v}
+    if override:
+        wl = WL.scaled(wl, **override)
     torch.cuda.set_device(0)
     inp = WL.make_inputs(wl)
     dv = misa.to_device(inp)
@@ -172,6 +177,17 @@ def main() -> int:
         dt = time.perf_counter() - t0
         assert torch.equal(ix.idx, expect), "graph replay differs from the eager step"
 
+    # Outside the timed region: which fraction of the dense all-head selection (Eq. dsa_topk)
+    # the routed selection recovered, both computed by the library on the same inputs.
+    from dataclasses import replace
+    from paper_2605_07363_amd.recall_sweep import overlap
+    dense = misa.Indexer(replace(p, h=p.H), wl.k)
+    dense.score(Q, W, Ks[0], scales[0], dense=True)
+    dense.select()
+    rows = wl.n_seq * wl.n_q
+    recall = overlap(ix.idx.view(rows, -1), dense.idx.view(rows, -1))
+    del dense
+
     ms_per_step = dt / args.steps * 1e3
     pairs = wl.pairs()
     stage_ms = {n: sum(e[j][0].elapsed_time(e[j][1]) for e in events) / args.steps
@@ -196,13 +212,15 @@ def main() -> int:
         "value": pairs / (dt / args.steps), "unit": "pairs/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32" if wl.k_dtype == "f32" else "bf16", "data": "synthetic",
-        "config": {"workload": f"{wl.name}: {DESCRIPTIONS[wl.name]}", "pairs_per_step": pairs,
+        "config": {"workload": f"{wl.name}: {DESCRIPTIONS[wl.name]}"
+                               + (f" [overridden: {override}]" if override else ""), "pairs_per_step": pairs,
                    "key_cache_bytes": key_bytes, "key_buffers_rotated": n_rot},
         "launch": "hip-graph replay of the whole step" if use_graph else "eager",
         "eager_ms_per_step": eager_ms,
         "stage_ms": stage_ms,
         "score_stage_pairs_per_s": pairs / score_s,
         "roofline": roof,
+        "recall_of_dense_topk": recall,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, inp)

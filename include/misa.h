@@ -110,7 +110,8 @@ int32_t misa_version(void);
  * blocks; block b covers tokens b*B .. min((b+1)*B, len_i) - 1 and Kp[i, b, :]
  * is the arithmetic mean of its (de-quantised) keys, fp32.  A partial last
  * block is averaged over the tokens it holds; blocks entirely past len_i are
- * written as zeros.
+ * written as zeros.  Blocks longer than 2048 tokens are summed in slices that
+ * pass through ws (MISA_OP_POOL reports its size, 0 for shorter blocks).
  *   K       in   [n_seq, L, d]
  *   kscale  in   [n_seq, L] (FP8 keys only, else NULL)
  *   Kp      out  [n_seq, M, d] float

@@ -78,6 +78,7 @@ misa_status hip_result(hipError_t e, const char* what) {
 
 size_t ws_bytes_for(const misa::Prob& pr, int op, int k) {
   switch (op) {
+    case MISA_OP_POOL: return misa::pool_ws_bytes(pr);
     case MISA_OP_ROUTE: return misa::route_ws_bytes(pr);
     case MISA_OP_TOPK: return misa::topk_ws_bytes(pr, k);
     case MISA_OP_RERANK:
@@ -103,13 +104,13 @@ size_t misa_workspace_bytes(const misa_problem* p, int32_t op, int32_t k) {
 
 misa_status misa_pool_keys(const misa_problem* p, const void* K, const float* kscale, float* Kp,
                            void* ws, size_t ws_bytes, void* stream) {
-  (void)ws; (void)ws_bytes;
   misa::Prob pr;
   misa_status st = check_problem(p, &pr);
   if (st != MISA_OK) return st;
   if ((st = check_keys(p, K, kscale)) != MISA_OK) return st;
   if (!Kp) return fail(MISA_ERR_INVALID_ARG, "Kp is NULL");
-  return hip_result(misa::launch_pool(pr, p->k_dtype, K, kscale, Kp, (hipStream_t)stream),
+  if ((st = check_ws(ws_bytes_for(pr, MISA_OP_POOL, 0), ws, ws_bytes)) != MISA_OK) return st;
+  return hip_result(misa::launch_pool(pr, p->k_dtype, K, kscale, Kp, ws, (hipStream_t)stream),
                     "misa_pool_keys launch");
 }
 

@@ -6,8 +6,9 @@
 
 namespace misa {
 
+size_t pool_ws_bytes(const Prob& p);
 hipError_t launch_pool(const Prob& p, int k_dtype, const void* K, const float* kscale, float* Kp,
-                       hipStream_t st);
+                       void* ws, hipStream_t st);
 
 int route_splits(const Prob& p);
 size_t route_ws_bytes(const Prob& p);

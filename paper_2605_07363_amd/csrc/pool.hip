@@ -1,6 +1,10 @@
 // Stage 1: block mean pooling of the indexer keys (Eq. pool).
 //
-// One workgroup per (pooled block, sequence).  The block's rows are streamed
+// One workgroup per (pooled block, sequence) - or, for blocks longer than 2048
+// tokens, per 1024-token slice of a block, whose fp32 partial sums go through
+// the workspace and are added in a fixed order by a second small kernel, so
+// that a few huge blocks (B up to the whole prefix) still fill the chip and
+// the result stays deterministic.  The block's rows are streamed
 // with 16-byte loads, a row being covered by 128/N consecutive lanes, so every
 // wavefront load instruction reads whole contiguous rows.  Each thread sums a
 // strided subset of rows in fp32; the subsets are combined through LDS in a
@@ -9,8 +13,13 @@
 
 namespace misa {
 
+constexpr int kPoolSlice = 1024;    // tokens per slice of a long block
+constexpr int kPoolSplitFrom = 2048;  // blocks longer than this are sliced
+
+// slices == 1: Kp receives the block means.  slices > 1: blockIdx.x = block * slices + slice
+// and `Kp` is the workspace [n_seq, M, slices, 128] of partial SUMS.
 template <int DT>
-__global__ __launch_bounds__(256) void pool_kernel(Prob p, const void* __restrict__ K,
+__global__ __launch_bounds__(256) void pool_kernel(Prob p, int slices, const void* __restrict__ K,
                                                    const float* __restrict__ kscale,
                                                    float* __restrict__ Kp) {
   using V = Vec16<DT>;
@@ -19,10 +28,12 @@ __global__ __launch_bounds__(256) void pool_kernel(Prob p, const void* __restric
   constexpr int RPP = 256 / TPR;      // rows per pass of the workgroup
   __shared__ float red[RPP][kD];
 
-  const int b = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
+  const int b = blockIdx.x / slices, slice = blockIdx.x % slices, seq = blockIdx.y, tid = threadIdx.x;
   const int len = seq_length(p, seq);
-  const long long lo = (long long)b * p.B;
-  const long long hi = min(lo + (long long)p.B, (long long)len);
+  const long long blo = (long long)b * p.B;
+  const long long bhi = min(blo + (long long)p.B, (long long)len);
+  const long long lo = slices == 1 ? blo : blo + (long long)slice * kPoolSlice;
+  const long long hi = slices == 1 ? bhi : min(lo + kPoolSlice, bhi);
   const int c = tid % TPR, r = tid / TPR;
 
   float acc[N];
@@ -45,19 +56,61 @@ __global__ __launch_bounds__(256) void pool_kernel(Prob p, const void* __restric
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < RPP; ++i) s += red[i][tid];
-    const long long cnt = hi - lo;
-    Kp[((size_t)seq * p.M + b) * kD + tid] = cnt > 0 ? s / (float)cnt : 0.f;
+    if (slices == 1) {
+      const long long cnt = hi - lo;
+      Kp[((size_t)seq * p.M + b) * kD + tid] = cnt > 0 ? s / (float)cnt : 0.f;
+    } else {
+      Kp[(((size_t)seq * p.M + b) * slices + slice) * kD + tid] = s;  // empty slices write 0
+    }
   }
 }
 
-hipError_t launch_pool(const Prob& p, int k_dtype, const void* K, const float* kscale, float* Kp,
-                       hipStream_t st) {
-  const dim3 grid(p.M, p.n_seq), block(256);
-  switch (k_dtype) {
-    case MISA_F32: pool_kernel<MISA_F32><<<grid, block, 0, st>>>(p, K, kscale, Kp); break;
-    case MISA_BF16: pool_kernel<MISA_BF16><<<grid, block, 0, st>>>(p, K, kscale, Kp); break;
-    default: pool_kernel<MISA_FP8_E4M3><<<grid, block, 0, st>>>(p, K, kscale, Kp); break;
+// Adds the slice sums of every block in a fixed order (eight interleaved
+// subsets, then those in order) and divides by the token count.
+__global__ __launch_bounds__(1024) void pool_combine_kernel(Prob p, int slices,
+                                                            const float* __restrict__ part,
+                                                            float* __restrict__ Kp) {
+  __shared__ float red[8][kD];
+  const int b = blockIdx.x, seq = blockIdx.y, c = threadIdx.x % kD, g = threadIdx.x / kD;
+  const float* src = part + ((size_t)seq * p.M + b) * slices * kD + c;
+  float s = 0.f;
+#pragma unroll 4
+  for (int i = g; i < slices; i += 8) s += src[(size_t)i * kD];
+  red[g][c] = s;
+  __syncthreads();
+  if (g == 0) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t += red[i][c];
+    const int len = seq_length(p, seq);
+    const long long lo = (long long)b * p.B;
+    const long long cnt = min(lo + (long long)p.B, (long long)len) - lo;
+    Kp[((size_t)seq * p.M + b) * kD + c] = cnt > 0 ? t / (float)cnt : 0.f;
   }
+}
+
+static int pool_slices(const Prob& p) {
+  return p.B > kPoolSplitFrom ? (int)(((long long)min(p.B, p.L) + kPoolSlice - 1) / kPoolSlice) : 1;
+}
+
+size_t pool_ws_bytes(const Prob& p) {
+  const int sl = pool_slices(p);
+  return sl == 1 ? 0 : (size_t)p.n_seq * p.M * sl * kD * sizeof(float);
+}
+
+hipError_t launch_pool(const Prob& p, int k_dtype, const void* K, const float* kscale, float* Kp,
+                       void* ws, hipStream_t st) {
+  const int sl = pool_slices(p);
+  const dim3 grid(p.M * sl, p.n_seq), block(256);
+  float* dst = sl == 1 ? Kp : static_cast<float*>(ws);
+  switch (k_dtype) {
+    case MISA_F32: pool_kernel<MISA_F32><<<grid, block, 0, st>>>(p, sl, K, kscale, dst); break;
+    case MISA_BF16: pool_kernel<MISA_BF16><<<grid, block, 0, st>>>(p, sl, K, kscale, dst); break;
+    default: pool_kernel<MISA_FP8_E4M3><<<grid, block, 0, st>>>(p, sl, K, kscale, dst); break;
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || sl == 1) return e;
+  pool_combine_kernel<<<dim3(p.M, p.n_seq), 1024, 0, st>>>(p, sl, dst, Kp);
   return hipGetLastError();
 }
 

@@ -33,6 +33,11 @@ CASES = {
     "f32_prefill": WL.scaled(WL.WORKLOADS["c0"], L=700, n_q=9, decode=False, B=50, k=64, needles=4),
     "bf16_bigB": small("c1", n_seq=2, L=3000, B=5000, k=100),
     "bf16_B1": small("c1", n_seq=1, L=300, B=1, k=50, needles=4),
+    # block sizes of the paper's own sweep (B = 1024 ... one block for the whole prefix): the
+    # pooling kernel cuts such blocks into slices
+    "fp8_B1024": small("c3", n_seq=2, L=7000, B=1024, k=200, needles=8),
+    "bf16_B4096": small("c1", n_seq=3, L=9500, B=4096, k=200, needles=8),
+    "fp8_Bwhole": small("c3", n_seq=2, L=6000, B=6000, k=100, needles=8),
     "glm_dense_h": small("c3", n_seq=1, L=2000, h=32, B=128, k=100, needles=8),
     # other head-slot widths of the prefill kernel (h = 16, 32, 3) and tiny head counts
     "bf16_prefill_h16": small("c2", L=1500, n_q=21, h=16, B=64, k=100),
@@ -54,7 +59,8 @@ def ragged(wl):
 
 
 # --------------------------------------------------------------------- pool
-@pytest.mark.parametrize("name", ["f32_decode", "bf16_decode", "fp8_decode", "bf16_bigB", "bf16_B1"])
+@pytest.mark.parametrize("name", ["f32_decode", "bf16_decode", "fp8_decode", "bf16_bigB", "bf16_B1",
+                                  "fp8_B1024", "bf16_B4096", "fp8_Bwhole"])
 @pytest.mark.parametrize("use_len", [False, True])
 def test_pool_keys(misa, name, use_len):
     wl = CASES[name]
@@ -62,7 +68,7 @@ def test_pool_keys(misa, name, use_len):
     dv = misa.to_device(inp)
     p = dv["problem"]
     Kp = torch.full((wl.n_seq, p.M, wl.d), 7.0, dtype=torch.float32, device="cuda")
-    misa.pool_keys(p, dv["K"], dv["kscale"], Kp)
+    misa.pool_keys(p, dv["K"], dv["kscale"], Kp, misa.alloc_workspace(p, misa.OP_POOL))
     got = Kp.cpu().numpy()
     for s in range(wl.n_seq):
         K, _, _, n = oracle_view(inp, s, 0)

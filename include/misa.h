@@ -74,7 +74,8 @@ typedef enum misa_op {
   MISA_OP_ROUTE = 1,
   MISA_OP_SCORE = 2,
   MISA_OP_TOPK = 3,
-  MISA_OP_RERANK = 4
+  MISA_OP_RERANK = 4,
+  MISA_OP_SELECT = 5
 } misa_op;
 
 /* Problem description shared by all calls (host struct, passed by pointer). */
@@ -164,6 +165,35 @@ misa_status misa_score_tokens(const misa_problem* p, const void* Q, const float*
  */
 misa_status misa_topk(const misa_problem* p, const float* S, int32_t k, int32_t* idx,
                       float* val, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stages 3 + 4 in one call (Eq. misa_score then Eq. misa_topk / Eq.
+ * misa_candidate; heads == NULL: Eq. dsa_score then Eq. dsa_topk).  Writes
+ * exactly what misa_score_tokens followed by misa_topk would write to idx and
+ * val, but for many-query problems (bf16 queries, bf16 or FP8 keys, n_q >= 8,
+ * k <= 8192, L >= 4096) the [n_seq, n_q, L] score matrix is not produced:
+ * a 1/16 sample of the keys gives a per-row threshold, a second scoring pass
+ * keeps only the scores that reach it, and the exact top-k is taken from
+ * those.  Rows for which the threshold turns out too high or too low are
+ * recomputed by the two-call path inside the same call, so the result never
+ * depends on the sample.  Other problems run the two calls back to back.
+ * ws (MISA_OP_SELECT) includes room for the score matrix in both cases.
+ *   heads  in   [n_seq, n_q, h] int32 or NULL
+ *   idx    out  [n_seq, n_q, k] int32 ascending; unused tail slots = -1
+ *   val    out  [n_seq, n_q, k] float or NULL, tail = -inf
+ */
+misa_status misa_select_tokens(const misa_problem* p, const void* Q, const float* W,
+                               const int32_t* heads, const void* K, const float* kscale,
+                               int32_t k, int32_t* idx, float* val, void* ws, size_t ws_bytes,
+                               void* stream);
+
+/*
+ * Monitoring aid for misa_select_tokens: byte offset inside its workspace of
+ * an int32 array [n_seq, n_q] that the last call left there, 1 for every row
+ * that was recomputed by the two-call path and 0 otherwise; -1 if the problem
+ * does not take the sampled route at all.  routed: whether heads was non-NULL.
+ */
+int64_t misa_select_row_flags_offset(const misa_problem* p, int32_t routed, int32_t k);
 
 /*
  * Stage 5 - MISA-dagger fine stage (Eq. misa_final_topk): re-score the

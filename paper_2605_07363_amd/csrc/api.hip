@@ -76,8 +76,9 @@ misa_status hip_result(hipError_t e, const char* what) {
   return fail(MISA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-size_t ws_bytes_for(const misa::Prob& pr, int op, int k) {
+size_t ws_bytes_for(const misa::Prob& pr, int op, int k, int k_dtype = 0, int q_dtype = 0) {
   switch (op) {
+    case MISA_OP_SELECT: return misa::select_ws_bytes(pr, k_dtype, q_dtype, k);
     case MISA_OP_POOL: return misa::pool_ws_bytes(pr);
     case MISA_OP_ROUTE: return misa::route_ws_bytes(pr);
     case MISA_OP_TOPK: return misa::topk_ws_bytes(pr, k);
@@ -98,8 +99,8 @@ const char* misa_last_error(void) { return g_err; }
 size_t misa_workspace_bytes(const misa_problem* p, int32_t op, int32_t k) {
   misa::Prob pr;
   if (check_problem(p, &pr) != MISA_OK) return 0;
-  if (op < MISA_OP_POOL || op > MISA_OP_RERANK) return 0;
-  return ws_bytes_for(pr, op, k);
+  if (op < MISA_OP_POOL || op > MISA_OP_SELECT) return 0;
+  return ws_bytes_for(pr, op, k, p->k_dtype, p->q_dtype);
 }
 
 misa_status misa_pool_keys(const misa_problem* p, const void* K, const float* kscale, float* Kp,
@@ -155,6 +156,30 @@ misa_status misa_topk(const misa_problem* p, const float* S, int32_t k, int32_t*
   if ((st = check_ws(ws_bytes_for(pr, MISA_OP_TOPK, k), ws, ws_bytes)) != MISA_OK) return st;
   return hip_result(misa::launch_topk(pr, S, pr.L, k, nullptr, idx, val, ws, (hipStream_t)stream),
                     "misa_topk launch");
+}
+
+misa_status misa_select_tokens(const misa_problem* p, const void* Q, const float* W,
+                               const int32_t* heads, const void* K, const float* kscale, int32_t k,
+                               int32_t* idx, float* val, void* ws, size_t ws_bytes, void* stream) {
+  misa::Prob pr;
+  misa_status st = check_problem(p, &pr);
+  if (st != MISA_OK) return st;
+  if ((st = check_queries(Q, W)) != MISA_OK) return st;
+  if ((st = check_keys(p, K, kscale)) != MISA_OK) return st;
+  if (!idx) return fail(MISA_ERR_INVALID_ARG, "idx is NULL");
+  if (k < 1) return fail(MISA_ERR_INVALID_ARG, "k must be >= 1 (got %d)", k);
+  if (k > misa::kMaxTopK) return fail(MISA_ERR_UNSUPPORTED, "k must be <= 16384 (got %d)", k);
+  if ((st = check_ws(ws_bytes_for(pr, MISA_OP_SELECT, k, p->k_dtype, p->q_dtype), ws, ws_bytes)) != MISA_OK)
+    return st;
+  return hip_result(misa::launch_select(pr, p->k_dtype, p->q_dtype, Q, W, heads, K, kscale, k, idx, val,
+                                        ws, (hipStream_t)stream),
+                    "misa_select_tokens launch");
+}
+
+int64_t misa_select_row_flags_offset(const misa_problem* p, int32_t routed, int32_t k) {
+  misa::Prob pr;
+  if (check_problem(p, &pr) != MISA_OK) return -1;
+  return misa::select_row_flags_offset(pr, p->k_dtype, p->q_dtype, routed != 0, k);
 }
 
 misa_status misa_rerank(const misa_problem* p, const void* Q, const float* W, const void* K,

@@ -22,13 +22,39 @@ hipError_t launch_score(const Prob& p, int k_dtype, int q_dtype, const void* Q, 
                         const int* heads, const void* K, const float* kscale, const int* cand,
                         int k_cand, float* out, hipStream_t st);
 
+// The prefill (matrix-core tile) scoring kernel in its three modes; see score.hip.
+enum { kTileStore = 0, kTileSample = 1, kTileFilter = 2 };
+constexpr int kSampleStride = 16;
+struct TileAux {
+  const int* run = nullptr;     // store mode: per query tile, 0 = skip the tile (nullptr: run all)
+  const float* tau = nullptr;   // filter mode: per-row score threshold
+  int2* cand = nullptr;         // filter mode: [rows, cap] (key index, score bits)
+  int* count = nullptr;         // filter mode: per-row candidate count (may exceed cap: overflow)
+  int cap = 0;
+};
+bool tile_path(const Prob& p, int k_dtype, int q_dtype);  // launch_score uses the tile kernel
+int tile_queries_per_wg(const Prob& p, bool routed);
+hipError_t launch_tile_mode(const Prob& p, int k_dtype, int mode, const TileAux& aux, const void* Q,
+                            const float* W, const int* heads, const void* K, const float* kscale,
+                            float* S, hipStream_t st);
+
+// Fused scoring + top-k (scores are not materialised on the common path).
+size_t select_ws_bytes(const Prob& p, int k_dtype, int q_dtype, int k);
+// Byte offset in the workspace of the per-row int flags (1 = the row was repaired by the
+// two-call path) that the last launch_select left, or -1 when the problem is not fused.
+long long select_row_flags_offset(const Prob& p, int k_dtype, int q_dtype, bool routed, int k);
+hipError_t launch_select(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,
+                         const int* heads, const void* K, const float* kscale, int k, int* idx,
+                         float* val, void* ws, hipStream_t st);
+
 // Top-k of rows of length row_len.  map == nullptr: row r scans its visible
 // prefix and reports positions.  map != nullptr (re-rank): row r scans all
 // row_len slots, never selects -inf slots and reports map[slot].
 constexpr int kMaxTopK = 16384;
 constexpr int kMaxRowLen = 524288;
 size_t topk_ws_bytes(const Prob& p, int k);
+// only != nullptr: rows r with only[r] == 0 are left untouched (ws is not needed then).
 hipError_t launch_topk(const Prob& p, const float* S, int row_len, int k, const int* map, int* idx,
-                       float* val, void* ws, hipStream_t st);
+                       float* val, void* ws, hipStream_t st, const int* only = nullptr);
 
 }  // namespace misa

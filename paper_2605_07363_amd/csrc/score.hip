@@ -17,6 +17,7 @@
 // score_generic_kernel: plain fp32 FMA path for every other combination
 //   (fp32 inputs, candidate lists).  One thread per key or candidate; the
 //   gathered query heads sit in LDS and are read by broadcast.
+#include <algorithm>
 #include <type_traits>
 
 #include "kernels.h"
@@ -295,30 +296,53 @@ struct TileGeom {
 };
 
 constexpr int kKT = 64;  // keys per LDS tile
+// Queries per sequence from which the tiled matrix-core kernel is used.
+constexpr int kTileMinQueries = 8;
+constexpr int kStageCap = 256;  // filter mode: staged candidates per wavefront and pair of queries
 
-template <int KDT, int HS>
-__global__ __launch_bounds__(256) void score_tile_kernel(
-    Prob p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
+// MODE kTileStore: scores of all keys go to S [rows, L].
+// MODE kTileSample: only one key of every group of kSampleStride consecutive
+//   keys is scored (at a hashed position inside its group); the result is a
+//   score matrix [rows, L / kSampleStride] in which a query sees the first
+//   n / kSampleStride entries.
+// MODE kTileFilter: nothing is stored densely; (key, score) pairs whose score
+//   reaches the row's threshold aux.tau are appended to the row's candidate
+//   list.  A wavefront owns its queries, so it collects their candidates in
+//   private LDS staging lists with ballot-computed slots (one list per pair of
+//   queries that share an accumulator slot in the two half-waves, entries tagged
+//   with the half) and moves them to the global lists in batches, one global
+//   atomic per query and batch.
+// The work of one workgroup: query tile q_tile of sequence blockIdx.z, key range blockIdx.x.
+template <int KDT, int HS, int MODE>
+__device__ __forceinline__ void score_tile_body(
+    const Prob& p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
-    float* __restrict__ S) {
+    float* __restrict__ S, const TileAux& aux, int q_tile) {
   using G = TileGeom<HS>;
   constexpr int RT = G::RT, QW = G::QW, QWG = G::QWG;
+  constexpr bool FILTER = MODE == kTileFilter, SAMPLE = MODE == kTileSample;
+  constexpr int NQL_ = HS == 8 ? RT * 2 : (HS == 16 ? RT : 1);  // queries per lane
   constexpr int ROW_BYTES = KDT == MISA_BF16 ? 256 : 128;
   constexpr int NLD = KDT == MISA_BF16 ? 4 : 2;  // 16-byte global loads per thread and tile
   __shared__ uint4 ktile[2][kKT * 16];
   __shared__ float kscl[2][kKT];
   __shared__ int nvis[QWG];
   __shared__ int s_head[QWG][HS];
+  __shared__ int2 stg[FILTER ? 4 * NQL_ * kStageCap : 1];
 
+  const int LT = SAMPLE ? p.L / kSampleStride : p.L;  // keys in tile space
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, hf = lane >> 5;
   const int seq = blockIdx.z;
-  const int q_base = blockIdx.y * QWG;
+  const int q_base = q_tile * QWG;
   const int k_begin = blockIdx.x * keys_per_wg;
-  const int k_end = min(k_begin + keys_per_wg, p.L);
+  const int k_end = min(k_begin + keys_per_wg, LT);
   const int hc = heads ? p.h : p.H;
 
-  for (int i = tid; i < QWG; i += 256) nvis[i] = q_base + i < p.n_q ? visible(p, seq, q_base + i) : 0;
+  for (int i = tid; i < QWG; i += 256) {
+    const int n = q_base + i < p.n_q ? visible(p, seq, q_base + i) : 0;
+    nvis[i] = SAMPLE ? n / kSampleStride : n;
+  }
   for (int i = tid; i < QWG * HS; i += 256) {
     const int qi = i / HS, slot = i % HS, q = q_base + qi;
     int head = -1;
@@ -362,15 +386,22 @@ __global__ __launch_bounds__(256) void score_tile_kernel(
   constexpr int CPR = ROW_BYTES / 16;  // chunks per key row
   uint4 st0 = make_uint4(0, 0, 0, 0), st1 = st0, st2 = st0, st3 = st0;
   float st_scale = 1.f;
+  // Cache row of key j of tile space (clamped into the cache).  Sampling takes key
+  // 16 j + (top four bits of a multiplicative hash of j) of every group of 16.
+  auto key_row = [&](int j) -> size_t {
+    j = min(j, LT - 1);
+    if (SAMPLE) return (size_t)j * kSampleStride + (((uint32_t)j * 2654435761u) >> 28);
+    return (size_t)j;
+  };
 #define MISA_TILE_LOAD(k0)                                                                        \
   do {                                                                                            \
-    st0 = *reinterpret_cast<const uint4*>(kbase + (size_t)min((k0) + tid / CPR, p.L - 1) * ROW_BYTES + (tid % CPR) * 16); \
-    st1 = *reinterpret_cast<const uint4*>(kbase + (size_t)min((k0) + (tid + 256) / CPR, p.L - 1) * ROW_BYTES + (tid % CPR) * 16); \
+    st0 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + tid / CPR) * ROW_BYTES + (tid % CPR) * 16); \
+    st1 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 256) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
     if (NLD == 4) {                                                                               \
-      st2 = *reinterpret_cast<const uint4*>(kbase + (size_t)min((k0) + (tid + 512) / CPR, p.L - 1) * ROW_BYTES + (tid % CPR) * 16); \
-      st3 = *reinterpret_cast<const uint4*>(kbase + (size_t)min((k0) + (tid + 768) / CPR, p.L - 1) * ROW_BYTES + (tid % CPR) * 16); \
+      st2 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 512) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
+      st3 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 768) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
     }                                                                                             \
-    if (KDT == MISA_FP8_E4M3 && tid < kKT) st_scale = kscale[(size_t)seq * p.L + min((k0) + tid, p.L - 1)]; \
+    if (KDT == MISA_FP8_E4M3 && tid < kKT) st_scale = kscale[(size_t)seq * p.L + key_row((k0) + tid)]; \
   } while (0)
   auto put_chunk = [&](int b, int chunk, const uint4& v) {  // registers -> LDS, bf16, XOR (row & 15)
     const int row = chunk / CPR, c = chunk % CPR;
@@ -400,17 +431,61 @@ __global__ __launch_bounds__(256) void score_tile_kernel(
   // queries this lane reports: prefix lengths and 32-bit offsets of their score
   // rows relative to the first row of the tile (uniform base + lane offset stores)
   constexpr int NQL = HS == 8 ? RT * 2 : (HS == 16 ? RT : 1);  // queries per lane
-  float* s_tile = S + ((size_t)seq * p.n_q + q_base) * p.L;
+  float* s_tile = S + ((size_t)seq * p.n_q + q_base) * LT;
   int qn[NQL];
   uint32_t qoff[NQL];
+  // filter mode: thresholds of this lane's queries and the lengths of the wavefront's
+  // staging lists (wavefront-uniform, so they live in scalar registers)
+  float tauv[NQL];
+  int cnt[NQL];
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   int n_min = 0x7FFFFFFF;
 #pragma unroll
   for (int j = 0; j < NQL; ++j) {
     const int qi = wave * QW + (HS == 8 ? (j >> 1) * 4 + hf * 2 + (j & 1) : (HS == 16 ? j * 2 + hf : hf));
     const bool ok = q_base + qi < p.n_q;
     qn[j] = ok ? nvis[qi] : -1;   // -1: query does not exist, nothing is stored
-    qoff[j] = (uint32_t)qi * (uint32_t)p.L;
+    qoff[j] = (uint32_t)qi * (uint32_t)LT;
+    cnt[j] = 0;
+    tauv[j] = INFINITY;
+    if (FILTER && ok) tauv[j] = aux.tau[(size_t)seq * p.n_q + q_base + qi];
   }
+  // Moves staging list j (the candidates of the two queries in accumulator slot j of the
+  // lower and of the upper half-wave) to the global lists of those queries.
+  auto flush_list = [&](int j) {
+    const int c = cnt[j];
+    const int2* src = stg + (wave_u * NQL + j) * kStageCap;
+    // entries of each query: first the totals, then one atomic per query reserves the room
+    int tot[2] = {0, 0};
+    for (int i0 = 0; i0 < c; i0 += 64) {
+      const bool in = i0 + lane < c;
+      const bool up = in && src[min(i0 + lane, c - 1)].x < 0;
+      const int n_up = __popcll(__ballot(up));
+      tot[1] += n_up;
+      tot[0] += min(64, c - i0) - n_up;
+    }
+    const int qi = wave_u * QW + (HS == 8 ? (j >> 1) * 4 + (lane & 1) * 2 + (j & 1) : (HS == 16 ? j * 2 + (lane & 1) : (lane & 1)));
+    const size_t my_row = (size_t)seq * p.n_q + q_base + qi;   // lanes 0 and 1: the two queries
+    int base = 0;
+    const int mine = lane == 0 ? tot[0] : tot[1];
+    if (lane < 2 && mine > 0) base = atomicAdd(&aux.count[my_row], mine);
+    int run[2] = {__shfl(base, 0), __shfl(base, 1)};
+    const long long row0 = __shfl((long long)my_row, 0), row1 = __shfl((long long)my_row, 1);
+    for (int i0 = 0; i0 < c; i0 += 64) {
+      const bool in = i0 + lane < c;
+      int2 e = src[min(i0 + lane, c - 1)];
+      const bool up = in && e.x < 0, down = in && e.x >= 0;
+      const unsigned long long mu = __ballot(up), md = __ballot(down);
+      const int pos = up ? run[1] + __popcll(mu & ((1ull << lane) - 1ull))
+                         : run[0] + __popcll(md & ((1ull << lane) - 1ull));
+      e.x &= 0x7FFFFFFF;
+      if (in && pos < aux.cap) aux.cand[(up ? row1 : row0) * aux.cap + pos] = e;
+      run[1] += __popcll(mu);
+      run[0] += __popcll(md);
+    }
+    cnt[j] = 0;
+  };
+
   for (int i = 0; i < QWG; ++i) n_min = min(n_min, q_base + i < p.n_q ? nvis[i] : -1);
   // tiles that end at or before plain_end are visible to every query of the
   // workgroup, all of which exist: no masks are needed there
@@ -457,7 +532,18 @@ __global__ __launch_bounds__(256) void score_tile_kernel(
 #pragma unroll
       for (int j = 0; j < NQL; ++j) out[j] *= scale;
     }
-    if (PLAIN) {
+    if (FILTER) {
+#pragma unroll
+      for (int j = 0; j < NQL; ++j) {
+        const bool pass = out[j] >= tauv[j] && (PLAIN || (key < k_end && key < qn[j]));
+        const unsigned long long m = __ballot(pass);
+        // list length + passing lanes below this one
+        const int slot = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, cnt[j]));
+        if (pass)
+          stg[(wave_u * NQL + j) * kStageCap + slot] = make_int2(key | (int)((uint32_t)hf << 31), __float_as_int(out[j]));
+        cnt[j] += __popcll(m);
+      }
+    } else if (PLAIN) {
 #pragma unroll
       for (int j = 0; j < NQL; ++j) s_tile[qoff[j] + (uint32_t)key] = out[j];
     } else {
@@ -477,6 +563,10 @@ __global__ __launch_bounds__(256) void score_tile_kernel(
     for (int i = 0; i < 8 * RT; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
       __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);     // ten VALU
+      if (FILTER) {
+        __builtin_amdgcn_sched_group_barrier(0x004, 2, 0);    // ballot bookkeeping
+        if (i % 4 == 3) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // a staged candidate write
+      }
     }
   };
 
@@ -517,20 +607,53 @@ __global__ __launch_bounds__(256) void score_tile_kernel(
       } else {
         epilogue(tag, accB, k0 + 32 + col, scaleB);
       }
+      if (FILTER) {
+#pragma unroll
+        for (int j = 0; j < NQL; ++j)     // up to 2 kKT entries per list and key tile
+          if (cnt[j] > kStageCap - 2 * kKT) flush_list(j);
+      }
     };
     // leading tiles that need no masks, then the rest
     const int n_plain = min(n_tiles, max(0, (plain_end - k_begin) / kKT));
     for (int i = 0; i < n_plain; ++i) body(Yes{}, i);
     for (int i = n_plain; i < n_tiles; ++i) body(No{}, i);
+    if (FILTER) {
+#pragma unroll
+      for (int j = 0; j < NQL; ++j)
+        if (cnt[j] > 0) flush_list(j);
+    }
   }
 #undef MISA_TILE_LOAD
 #undef MISA_TILE_STORE
+  if (MODE != kTileStore) return;
   // keys of this range that no query of the tile can see
   const int done = k_begin < k_stop ? k_begin + (k_stop - k_begin + kKT - 1) / kKT * kKT : k_begin;
 #pragma unroll
   for (int j = 0; j < NQL; ++j) {
     if (qn[j] < 0) continue;
     for (int key = done + col; key < k_end; key += 32) s_tile[qoff[j] + (uint32_t)key] = -INFINITY;
+  }
+}
+
+template <int KDT, int HS, int MODE>
+__global__ __launch_bounds__(256) void score_tile_kernel(
+    Prob p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
+    const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
+    float* __restrict__ S, TileAux aux) {
+  score_tile_body<KDT, HS, MODE>(p, keys_per_wg, Q, W, heads, K, kscale, S, aux, blockIdx.y);
+}
+
+// Store mode for the flagged query tiles only (aux.run).  Normally none is
+// flagged, so the grid is kept small: blockIdx.y strides over the query tiles.
+template <int KDT, int HS>
+__global__ __launch_bounds__(256) void score_tile_repair_kernel(
+    Prob p, int keys_per_wg, int q_tiles, const uint16_t* __restrict__ Q,
+    const float* __restrict__ W, const int* __restrict__ heads, const void* __restrict__ K,
+    const float* __restrict__ kscale, float* __restrict__ S, TileAux aux) {
+  for (int qt = blockIdx.y; qt < q_tiles; qt += gridDim.y) {
+    if (!aux.run[blockIdx.z * q_tiles + qt]) continue;
+    score_tile_body<KDT, HS, kTileStore>(p, keys_per_wg, Q, W, heads, K, kscale, S, aux, qt);
+    __syncthreads();
   }
 }
 
@@ -682,21 +805,41 @@ static hipError_t launch_stream(const Prob& p, const void* Q, const float* W, co
   return hipGetLastError();
 }
 
-template <int KDT>
+int tile_queries_per_wg(const Prob& p, bool routed) {
+  const int hc = routed ? p.h : p.H;
+  return hc <= 8 ? 32 : (hc <= 16 ? 16 : 8);
+}
+
+template <int KDT, int MODE>
 static hipError_t launch_tile(const Prob& p, const void* Q, const float* W, const int* heads,
-                              const void* K, const float* kscale, float* S, hipStream_t st) {
+                              const void* K, const float* kscale, float* S, const TileAux& aux,
+                              hipStream_t st) {
   const int hc = heads ? p.h : p.H;
   const int hs = hc <= 8 ? 8 : (hc <= 16 ? 16 : (hc <= 32 ? 32 : 64));
-  const int qwg = hs == 8 ? 32 : (hs == 16 ? 16 : 8);
+  const int qwg = tile_queries_per_wg(p, heads != nullptr);
   const int q_tiles = (p.n_q + qwg - 1) / qwg;
+  const int lt = MODE == kTileSample ? p.L / kSampleStride : p.L;  // keys in tile space
   // Key ranges: a multiple of 8 (one set per XCD), enough workgroups to fill
   // the chip several times, at least 1024 keys each.
   int splits = 8;
-  while (splits < 64 && (long long)splits * q_tiles * p.n_seq < 2048 && p.L / (splits * 2) >= 1024) splits *= 2;
-  int keys_per_wg = ((p.L + splits - 1) / splits + kKT - 1) / kKT * kKT;
-  const dim3 grid((p.L + keys_per_wg - 1) / keys_per_wg, q_tiles, p.n_seq);
+  while (splits < 64 && (long long)splits * q_tiles * p.n_seq < 2048 && lt / (splits * 2) >= 1024) splits *= 2;
+  int keys_per_wg = ((lt + splits - 1) / splits + kKT - 1) / kKT * kKT;
+  dim3 grid((lt + keys_per_wg - 1) / keys_per_wg, q_tiles, p.n_seq);
   const uint16_t* q = static_cast<const uint16_t*>(Q);
-#define GO(HS) score_tile_kernel<KDT, HS><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S)
+  if (MODE == kTileStore && aux.run) {
+    // about one resident set of workgroups, each striding over the query tiles
+    grid.y = (unsigned)std::max(1, std::min(q_tiles, (int)(512 / ((long long)grid.x * p.n_seq))));
+#define GO(HS) score_tile_repair_kernel<KDT, HS><<<grid, 256, 0, st>>>(p, keys_per_wg, q_tiles, q, W, heads, K, kscale, S, aux)
+    switch (hs) {
+      case 8: GO(8); break;
+      case 16: GO(16); break;
+      case 32: GO(32); break;
+      default: GO(64); break;
+    }
+#undef GO
+    return hipGetLastError();
+  }
+#define GO(HS) score_tile_kernel<KDT, HS, MODE><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S, aux)
   switch (hs) {
     case 8: GO(8); break;
     case 16: GO(16); break;
@@ -707,8 +850,23 @@ static hipError_t launch_tile(const Prob& p, const void* Q, const float* W, cons
   return hipGetLastError();
 }
 
-// Queries per sequence from which the tiled matrix-core kernel is used.
-constexpr int kTileMinQueries = 8;
+bool tile_path(const Prob& p, int k_dtype, int q_dtype) {
+  return q_dtype == MISA_BF16 && k_dtype != MISA_F32 && p.n_q >= kTileMinQueries;
+}
+
+hipError_t launch_tile_mode(const Prob& p, int k_dtype, int mode, const TileAux& aux, const void* Q,
+                            const float* W, const int* heads, const void* K, const float* kscale,
+                            float* S, hipStream_t st) {
+#define GO(KD)                                                                                     \
+  switch (mode) {                                                                                  \
+    case kTileSample: return launch_tile<KD, kTileSample>(p, Q, W, heads, K, kscale, S, aux, st);   \
+    case kTileFilter: return launch_tile<KD, kTileFilter>(p, Q, W, heads, K, kscale, S, aux, st);   \
+    default: return launch_tile<KD, kTileStore>(p, Q, W, heads, K, kscale, S, aux, st);            \
+  }
+  if (k_dtype == MISA_BF16) GO(MISA_BF16)
+  GO(MISA_FP8_E4M3)
+#undef GO
+}
 
 template <int KDT>
 static hipError_t launch_gather(const Prob& p, const void* Q, const float* W, const void* K,
@@ -731,10 +889,8 @@ hipError_t launch_score(const Prob& p, int k_dtype, int q_dtype, const void* Q, 
     return launch_gather<MISA_FP8_E4M3>(p, Q, W, K, kscale, cand, k_cand, out, st);
   }
   const bool mfma_ok = !cand && q_dtype == MISA_BF16 && k_dtype != MISA_F32;
-  if (mfma_ok && p.n_q >= kTileMinQueries) {
-    if (k_dtype == MISA_BF16) return launch_tile<MISA_BF16>(p, Q, W, heads, K, kscale, out, st);
-    return launch_tile<MISA_FP8_E4M3>(p, Q, W, heads, K, kscale, out, st);
-  }
+  if (mfma_ok && p.n_q >= kTileMinQueries)
+    return launch_tile_mode(p, k_dtype, kTileStore, TileAux{}, Q, W, heads, K, kscale, out, st);
   if (mfma_ok) {
     if (k_dtype == MISA_BF16) return launch_stream<MISA_BF16>(p, Q, W, heads, K, kscale, out, st);
     return launch_stream<MISA_FP8_E4M3>(p, Q, W, heads, K, kscale, out, st);

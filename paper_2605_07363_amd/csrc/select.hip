@@ -1,0 +1,420 @@
+// Stages 3 + 4 in one call for many-query (prefill) problems: the indices of the
+// k best-scoring visible keys of every query (Eq. misa_score followed by Eq.
+// misa_topk; with all heads Eq. dsa_score / Eq. dsa_topk) without writing the
+// [rows, L] score matrix to memory and reading it back.
+//
+//   1. sample    The tile scoring kernel scores one key of every group of 16
+//                (1/16 of the work) into a small matrix.
+//   2. threshold Per row, the r-th largest sampled score tau is found (radix
+//                select, rounded down).  r is a little above k/16, so that with
+//                overwhelming probability at least k of all scores reach tau
+//                while only about 16 r do.  Rows with few visible keys get
+//                tau = -inf (everything is a candidate).
+//   3. filter    The tile scoring kernel runs over all keys and appends the
+//                (key, score) pairs with score >= tau to per-row lists.
+//   4. select    Per row, the exact top-k of the list (ties: lower index) is
+//                chosen by radix select in LDS and written in ascending index
+//                order.  Since every score >= tau is in the list, the result
+//                equals the top-k of the full row whenever the list holds at
+//                least k entries and did not overflow.
+//   5. repair    Rows for which that does not hold are flagged; the plain path
+//                (dense scores of their query tiles, then the row top-k) runs
+//                for them only.  Without flagged rows these two launches exit
+//                at once.  The result is therefore always exact; the sampling
+//                only decides how much work it takes.
+//
+// Everything is stream-ordered device work: no host read-back, so the call can
+// be captured in a HIP graph.
+#include <cmath>
+
+#include "kernels.h"
+#include "radix.h"
+
+namespace misa {
+
+constexpr int kFusedMaxK = 8192;          // the candidate list of a row is held in registers
+constexpr int kFusedMinL = 4096;
+
+// Rank of the sampled threshold: mean k/16 sampled scores lie among the top k; the
+// margin covers the sampling noise of that count (more than five standard deviations).
+static int sample_rank(int k) {
+  const double mu = (double)k / kSampleStride;
+  return (int)std::ceil(mu + 6.0 * std::sqrt(mu) + 8.0);
+}
+
+// List capacity: expected 16 r candidates plus six standard deviations, in units of 256.
+static int list_capacity(int k) {
+  const double r = sample_rank(k);
+  const double c = kSampleStride * r * (1.0 + 6.0 / std::sqrt(r));
+  return ((int)std::ceil(c) + 255) / 256 * 256;
+}
+
+static size_t select_lds_bytes(const Prob& p) {
+  const size_t nwords = ((size_t)p.L + 31) / 32;
+  return nwords * 8;  // selection bitmap and per-word prefix counts
+}
+
+static bool fused(const Prob& p, int k_dtype, int q_dtype, int k) {
+  return tile_path(p, k_dtype, q_dtype) && k <= kFusedMaxK && p.L >= kFusedMinL;
+}
+
+__device__ __forceinline__ float key_to_float(uint32_t key) {
+  return __uint_as_float((key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key);
+}
+
+// ---------------------------------------------------------------- threshold
+// Scans a wavefront's 2048-bin LDS histogram from the top: the bin d with
+// count(bins > d) < need <= count(bins >= d).  Lane l owns bins 2047 - 32 l ... 2016 - 32 l.
+// Returns d and leaves need - count(bins > d) in *rest.  All 64 lanes call it.
+__device__ __forceinline__ int wave_find_bin(const int* hist, int need, int* rest) {
+  const int lane = threadIdx.x & 63;
+  const int top = kBins - 1 - 32 * lane;
+  int local = 0;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) local += hist[top - i];
+  int inc = local;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int y = __shfl_up(inc, o);
+    if (lane >= o) inc += y;
+  }
+  int above = inc - local;
+  const bool mine = above < need && need <= inc;
+  int d = 0, r = 0;
+  if (mine) {
+    for (int i = 0; i < 32; ++i) {
+      const int c = hist[top - i];
+      if (need <= above + c) { d = top - i; r = need - above; break; }
+      above += c;
+    }
+  }
+  const int owner = __ffsll((long long)__ballot(mine)) - 1;
+  *rest = __shfl(r, owner);
+  return __shfl(d, owner);
+}
+
+// One wavefront per row: tau[row] = a value at or just below the r-th largest of the
+// row's visible sampled scores (the lower edge of its 22-bit radix bin, i.e. within
+// 2^-13 relative), so at least r samples reach it.  Also clears the row's candidate
+// count and repair flags.
+__global__ __launch_bounds__(256) void select_threshold_kernel(
+    Prob p, const float* __restrict__ Ss, int m, int r, int cap, int qwg, int q_tiles,
+    float* __restrict__ tau, int* __restrict__ count, int* __restrict__ row_flag,
+    int* __restrict__ tile_flag) {
+  __shared__ int hist_all[4][kBins];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= p.n_seq * p.n_q) return;
+  const int seq = row / p.n_q, t = row % p.n_q;
+  int* hist = hist_all[wave];
+  const int n = visible(p, seq, t);
+  if (lane == 0) {
+    count[row] = 0;
+    row_flag[row] = 0;
+    if (t % qwg == 0) tile_flag[seq * q_tiles + t / qwg] = 0;
+  }
+  if (n <= cap) {  // every visible key fits into the list
+    if (lane == 0) tau[row] = -INFINITY;
+    return;
+  }
+  const int ns = n / kSampleStride;  // visible samples; ns > cap / 16 >= r
+  const float* s = Ss + (size_t)row * m;
+  for (int i = lane; i < kBins; i += 64) hist[i] = 0;
+  __builtin_amdgcn_wave_barrier();
+  // eight loads per lane in flight before the first is used
+  auto scan = [&](auto f) {
+    for (int base = 0; base < ns; base += 512) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = base + u * 64 + lane;
+        v[u] = i < ns ? s[i] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (base + u * 64 + lane < ns) f(order_key(v[u]));
+    }
+  };
+  scan([&](uint32_t key) { atomicAdd(&hist[key >> 21], 1); });
+  __builtin_amdgcn_wave_barrier();
+  int need;
+  const uint32_t d1 = (uint32_t)wave_find_bin(hist, r, &need);
+  __builtin_amdgcn_wave_barrier();
+  for (int i = lane; i < kBins; i += 64) hist[i] = 0;
+  __builtin_amdgcn_wave_barrier();
+  scan([&](uint32_t key) {
+    if ((key >> 21) == d1) atomicAdd(&hist[(key >> 10) & 0x7FF], 1);
+  });
+  __builtin_amdgcn_wave_barrier();
+  int rest;
+  const uint32_t d2 = (uint32_t)wave_find_bin(hist, need, &rest);
+  if (lane == 0) tau[row] = key_to_float((d1 << 21) | (d2 << 10));
+}
+
+// ---------------------------------------------------------------- select
+// One workgroup of NT threads per row: exact top-k of the row's candidate list.
+// Thread t owns list entries t, t + NT, ... (at most EPT of them) and keeps them in
+// registers for all passes, so LDS only holds the histogram and the row bitmaps and
+// several rows share a compute unit.
+template <int NT, int EPT>
+__global__ __launch_bounds__(NT) void select_rows_kernel(
+    Prob p, const int2* __restrict__ cand, const int* __restrict__ count, int cap, int k, int qwg,
+    int q_tiles, int* __restrict__ idx, float* __restrict__ val, int* __restrict__ row_flag,
+    int* __restrict__ tile_flag) {
+  extern __shared__ uint32_t dyn[];  // selection bitmap, then the prefix count of every bitmap word
+  __shared__ int hist[kBins];
+  __shared__ int scan_scratch[32];
+  __shared__ int thr[3];
+  const int t = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
+  const size_t row = (size_t)seq * p.n_q + t;
+  const int n = visible(p, seq, t);
+  const int k_eff = min(k, n);
+  int* out_idx = idx + row * k;
+  float* out_val = val ? val + row * k : nullptr;
+  for (int i = k_eff + tid; i < k; i += NT) {
+    out_idx[i] = -1;
+    if (out_val) out_val[i] = -INFINITY;
+  }
+  if (k_eff == 0) return;
+  const int c = count[row];
+  if (c > cap || c < k_eff) {  // list overflowed or threshold too high: leave the row to the repair pass
+    if (tid == 0) {
+      row_flag[row] = 1;
+      tile_flag[seq * q_tiles + t / qwg] = 1;
+    }
+    return;
+  }
+  const int nwords = (n + 31) / 32;
+  uint32_t* sel = dyn;
+  int* wpre = reinterpret_cast<int*>(dyn + (p.L + 31) / 32);
+  // this thread's entries: index (-1 = none) and order-preserving key of the score
+  int ei[EPT];
+  uint32_t ek[EPT];
+  float ev[EPT];
+  const int2* src = cand + row * (size_t)cap;
+#pragma unroll
+  for (int u = 0; u < EPT; ++u) {
+    const int i = tid + u * NT;
+    int2 e = make_int2(-1, 0);
+    if (i < c) e = src[i];
+    ei[u] = e.x;
+    ev[u] = __int_as_float(e.y);
+    ek[u] = order_key(ev[u]);
+  }
+  for (int i = tid; i < nwords; i += NT) sel[i] = 0;
+  zero_hist_n<NT>(hist);  // ends with a barrier
+  auto mark = [&](int e) { atomicOr(&sel[e >> 5], 1u << (e & 31)); };
+
+  if (c == k_eff) {
+#pragma unroll
+    for (int u = 0; u < EPT; ++u)
+      if (ei[u] >= 0) mark(ei[u]);
+  } else {
+    // most significant digit first: 11 + 11 + 10 bits of the key
+#pragma unroll
+    for (int u = 0; u < EPT; ++u)
+      if (ei[u] >= 0) atomicAdd(&hist[ek[u] >> 21], 1);
+    __syncthreads();
+    find_threshold_bin_n<NT>(hist, k_eff, scan_scratch, thr);
+    const uint32_t d1 = thr[0];
+    int need = thr[1];
+    __syncthreads();
+    zero_hist_n<NT>(hist);
+#pragma unroll
+    for (int u = 0; u < EPT; ++u) {
+      if (ei[u] < 0) continue;
+      const uint32_t a = ek[u] >> 21;
+      if (a > d1) mark(ei[u]);
+      else if (a == d1) atomicAdd(&hist[(ek[u] >> 10) & 0x7FF], 1);
+    }
+    __syncthreads();
+    find_threshold_bin_n<NT>(hist, need, scan_scratch, thr);
+    const uint32_t pre22 = (d1 << 11) | (uint32_t)thr[0];
+    need = thr[1];
+    __syncthreads();
+    zero_hist_n<NT>(hist);
+#pragma unroll
+    for (int u = 0; u < EPT; ++u) {
+      if (ei[u] < 0 || (ek[u] >> 21) != d1) continue;
+      if ((ek[u] >> 10) > pre22) mark(ei[u]);
+      else if ((ek[u] >> 10) == pre22) atomicAdd(&hist[ek[u] & 0x3FF], 1);
+    }
+    __syncthreads();
+    find_threshold_bin_n<NT>(hist, need, scan_scratch, thr);
+    const uint32_t tkey = (pre22 << 10) | (uint32_t)thr[0];
+    need = thr[1];
+    const int ties = thr[2];
+    __syncthreads();
+    if (ties == need) {
+#pragma unroll
+      for (int u = 0; u < EPT; ++u)
+        if (ei[u] >= 0 && (ek[u] >> 10) == pre22 && ek[u] >= tkey) mark(ei[u]);
+    } else {
+      // More entries equal to the threshold value than places: the `need` lowest
+      // indices among them win, found by the same digit search on the (high, low)
+      // halves of the index with the bin order inverted.
+      zero_hist_n<NT>(hist);
+#pragma unroll
+      for (int u = 0; u < EPT; ++u) {
+        if (ei[u] < 0) continue;
+        if ((ek[u] >> 10) == pre22 && ek[u] > tkey) mark(ei[u]);
+        else if (ek[u] == tkey) atomicAdd(&hist[kBins - 1 - (ei[u] >> 10)], 1);
+      }
+      __syncthreads();
+      find_threshold_bin_n<NT>(hist, need, scan_scratch, thr);
+      const int hi_digit = kBins - 1 - thr[0];
+      need = thr[1];
+      __syncthreads();
+      zero_hist_n<NT>(hist);
+#pragma unroll
+      for (int u = 0; u < EPT; ++u) {
+        if (ei[u] < 0 || ek[u] != tkey) continue;
+        if ((ei[u] >> 10) < hi_digit) mark(ei[u]);
+        else if ((ei[u] >> 10) == hi_digit) atomicAdd(&hist[kBins - 1 - (ei[u] & 0x3FF)], 1);
+      }
+      __syncthreads();
+      find_threshold_bin_n<NT>(hist, need, scan_scratch, thr);
+      const int lo_digit = kBins - 1 - thr[0];
+#pragma unroll
+      for (int u = 0; u < EPT; ++u) {
+        if (ei[u] < 0 || ek[u] != tkey) continue;
+        if ((ei[u] >> 10) == hi_digit && (ei[u] & 0x3FF) <= lo_digit) mark(ei[u]);
+      }
+    }
+  }
+  __syncthreads();
+
+  // Output slot of a selected index = number of selected indices below it.
+  const int wpt = (nwords + NT - 1) / NT;
+  const int w_lo = min(tid * wpt, nwords), w_hi = min(w_lo + wpt, nwords);
+  int cnt = 0;
+  for (int w = w_lo; w < w_hi; ++w) cnt += __popc(sel[w]);
+  int total;
+  int pos = block_exclusive_scan(cnt, scan_scratch, &total);
+  for (int w = w_lo; w < w_hi; ++w) {
+    wpre[w] = pos;
+    pos += __popc(sel[w]);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < EPT; ++u) {
+    const int e = ei[u];
+    if (e < 0) continue;
+    const uint32_t bits = sel[e >> 5], bit = 1u << (e & 31);
+    if (!(bits & bit)) continue;
+    const int slot = wpre[e >> 5] + __popc(bits & (bit - 1u));
+    if (slot < k) {  // always true when the selection is consistent
+      out_idx[slot] = e;
+      if (out_val) out_val[slot] = ev[u];
+    }
+  }
+}
+
+// ---------------------------------------------------------------- host side
+namespace {
+
+struct Layout {
+  size_t S, sample, tau, count, row_flag, tile_flag, cand, total;
+  int m, cap, qwg, q_tiles;
+};
+
+size_t up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+Layout layout(const Prob& p, bool routed, int k) {
+  Layout l;
+  const size_t rows = (size_t)p.n_seq * p.n_q;
+  l.m = p.L / kSampleStride;
+  l.cap = list_capacity(k);
+  l.qwg = tile_queries_per_wg(p, routed);
+  l.q_tiles = (p.n_q + l.qwg - 1) / l.qwg;
+  size_t o = 0;
+  l.S = o;         o += up(rows * p.L * sizeof(float));
+  l.sample = o;    o += up(rows * l.m * sizeof(float));
+  l.tau = o;       o += up(rows * sizeof(float));
+  l.count = o;     o += up(rows * sizeof(int));
+  l.row_flag = o;  o += up(rows * sizeof(int));
+  l.tile_flag = o; o += up((size_t)p.n_seq * l.q_tiles * sizeof(int));
+  l.cand = o;      o += up(rows * l.cap * sizeof(int2));
+  l.total = o;
+  return l;
+}
+
+}  // namespace
+
+size_t select_ws_bytes(const Prob& p, int k_dtype, int q_dtype, int k) {
+  if (k < 1) return 0;
+  const size_t dense = up((size_t)p.n_seq * p.n_q * p.L * sizeof(float));
+  if (!fused(p, k_dtype, q_dtype, k)) return dense + up(topk_ws_bytes(p, k));
+  // the larger head count (unrouted call) gives the smaller query tiles, hence more flags
+  return layout(p, false, k).total;
+}
+
+long long select_row_flags_offset(const Prob& p, int k_dtype, int q_dtype, bool routed, int k) {
+  if (k < 1 || !fused(p, k_dtype, q_dtype, k)) return -1;
+  return (long long)layout(p, routed, k).row_flag;
+}
+
+hipError_t launch_select(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,
+                         const int* heads, const void* K, const float* kscale, int k, int* idx,
+                         float* val, void* ws, hipStream_t st) {
+  char* base = static_cast<char*>(ws);
+  if (!fused(p, k_dtype, q_dtype, k)) {
+    float* S = reinterpret_cast<float*>(base);
+    const size_t dense = up((size_t)p.n_seq * p.n_q * p.L * sizeof(float));
+    hipError_t e = launch_score(p, k_dtype, q_dtype, Q, W, heads, K, kscale, nullptr, 0, S, st);
+    if (e != hipSuccess) return e;
+    return launch_topk(p, S, p.L, k, nullptr, idx, val, base + dense, st);
+  }
+  const Layout l = layout(p, heads != nullptr, k);
+  float* S = reinterpret_cast<float*>(base + l.S);
+  float* Ss = reinterpret_cast<float*>(base + l.sample);
+  float* tau = reinterpret_cast<float*>(base + l.tau);
+  int* count = reinterpret_cast<int*>(base + l.count);
+  int* row_flag = reinterpret_cast<int*>(base + l.row_flag);
+  int* tile_flag = reinterpret_cast<int*>(base + l.tile_flag);
+  int2* cand = reinterpret_cast<int2*>(base + l.cand);
+  const dim3 rows(p.n_q, p.n_seq);
+
+  hipError_t e = launch_tile_mode(p, k_dtype, kTileSample, TileAux{}, Q, W, heads, K, kscale, Ss, st);
+  if (e != hipSuccess) return e;
+  select_threshold_kernel<<<(p.n_seq * p.n_q + 3) / 4, 256, 0, st>>>(
+      p, Ss, l.m, sample_rank(k), l.cap, l.qwg, l.q_tiles, tau, count, row_flag, tile_flag);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+
+  TileAux filter;
+  filter.tau = tau;
+  filter.cand = cand;
+  filter.count = count;
+  filter.cap = l.cap;
+  e = launch_tile_mode(p, k_dtype, kTileFilter, filter, Q, W, heads, K, kscale, nullptr, st);
+  if (e != hipSuccess) return e;
+
+  const size_t lds = select_lds_bytes(p);  // at most 128 KB (L <= 524288)
+#define GO(NT, EPT)                                                                                 \
+  do {                                                                                              \
+    static size_t attr = 48 * 1024; /* default dynamic LDS limit */                                 \
+    if (lds > attr) {                                                                               \
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_rows_kernel<NT, EPT>),           \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                \
+      if (e != hipSuccess) return e;                                                                \
+      attr = lds;                                                                                   \
+    }                                                                                               \
+    select_rows_kernel<NT, EPT><<<rows, NT, lds, st>>>(p, cand, count, l.cap, k, l.qwg, l.q_tiles,  \
+                                                       idx, val, row_flag, tile_flag);              \
+  } while (0)
+  // thread count per row by list size (measured on MI355X: 512 for lists up to 5120
+  // entries, 1024 above)
+  if (l.cap <= 5120) GO(512, 10);
+  else GO(1024, 13);  // list_capacity(kFusedMaxK) = 13056 <= 13 * 1024
+#undef GO
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+
+  // repair pass, a no-op unless rows were flagged
+  TileAux repair;
+  repair.run = tile_flag;
+  e = launch_tile_mode(p, k_dtype, kTileStore, repair, Q, W, heads, K, kscale, S, st);
+  if (e != hipSuccess) return e;
+  return launch_topk(p, S, p.L, k, nullptr, idx, val, nullptr, st, row_flag);
+}
+
+}  // namespace misa

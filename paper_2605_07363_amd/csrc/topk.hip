@@ -20,49 +20,13 @@
 // compacted lists in the workspace; topk_kernel<true> then finishes each row
 // from those lists.
 #include "kernels.h"
+#include "radix.h"
 
 namespace misa {
 
-constexpr int kTopkThreads = 1024;
-constexpr int kBins = 2048;
 constexpr int kCap = 7000;          // boundary list capacity (entries); sized so two workgroups share a CU
 constexpr int kChunk = 8192;        // row elements per workgroup in the split passes
 constexpr int kPreHeader = kBins + 64;  // hist, then n_certain, n_boundary, padding
-
-// Finds the digit d (scanning from the top) with count(digit > d) < need <= count(digit >= d).
-// Thread i owns bins 2047-2i and 2046-2i.  Writes {d, need - count(digit > d), hist[d]} to out.
-__device__ __forceinline__ void find_threshold_bin(const int* hist, int need, int* scan_scratch,
-                                                   int* out) {
-  const int tid = threadIdx.x;
-  const int ba = kBins - 1 - 2 * tid, bb = ba - 1;
-  const int ha = hist[ba], hb = hist[bb];
-  int total;
-  const int above = block_exclusive_scan(ha + hb, scan_scratch, &total);
-  if (above < need && need <= above + ha) {
-    out[0] = ba; out[1] = need - above; out[2] = ha;
-  } else if (above + ha < need && need <= above + ha + hb) {
-    out[0] = bb; out[1] = need - above - ha; out[2] = hb;
-  }
-  __syncthreads();
-}
-
-__device__ __forceinline__ void zero_hist(int* hist) {
-  for (int i = threadIdx.x; i < kBins; i += kTopkThreads) hist[i] = 0;
-  __syncthreads();
-}
-
-// Appends the flagged lanes' values to a list whose length counter lives at *counter
-// (LDS or global); one atomic per wavefront.  Returns the slot of this lane (or -1).
-__device__ __forceinline__ int wave_append(bool flag, int* counter) {
-  const unsigned long long mask = __ballot(flag);
-  if (mask == 0) return -1;
-  const int lane = threadIdx.x & 63;
-  const int leader = __ffsll((long long)mask) - 1;
-  int base = 0;
-  if (lane == leader) base = atomicAdd(counter, __popcll(mask));
-  base = __shfl(base, leader);
-  return flag ? base + __popcll(mask & ((1ull << lane) - 1ull)) : -1;
-}
 
 // Visits elements lo..hi-1 of a row with all threads of the block.  Eight
 // coalesced loads per thread are in flight before the first one is used.  f is
@@ -160,19 +124,17 @@ __global__ __launch_bounds__(kTopkThreads) void topk_partition_kernel(Prob p,
 
 // ---------------------------------------------------------------- per-row kernel
 template <bool PRE>
-__global__ __launch_bounds__(kTopkThreads) void topk_kernel(Prob p, const float* __restrict__ S,
-                                                            int row_len, int k,
-                                                            const int* __restrict__ map,
-                                                            int* __restrict__ idx,
-                                                            float* __restrict__ val,
-                                                            const int* __restrict__ pre) {
-  extern __shared__ uint32_t dyn[];  // sel bitmap, then eq bitmap OR boundary list (keys, idx)
+__device__ __forceinline__ void topk_row(const Prob& p, const float* __restrict__ S, int row_len,
+                                         int k, const int* __restrict__ map, int* __restrict__ idx,
+                                         float* __restrict__ val, const int* __restrict__ pre, int t,
+                                         int seq, uint32_t* dyn) {
+  // dyn: sel bitmap, then eq bitmap OR boundary list (keys, idx)
   __shared__ int hist[kBins];
   __shared__ int scan_scratch[32];
   __shared__ int thr[3];
   __shared__ int list_len;
 
-  const int t = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
+  const int tid = threadIdx.x;
   const size_t row = (size_t)seq * p.n_q + t;
   const float* s = S + row * row_len;
   const int n = map ? row_len : visible(p, seq, t);
@@ -388,6 +350,32 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(Prob p, const float*
   }
 }
 
+template <bool PRE>
+__global__ __launch_bounds__(kTopkThreads) void topk_kernel(Prob p, const float* __restrict__ S,
+                                                            int row_len, int k,
+                                                            const int* __restrict__ map,
+                                                            int* __restrict__ idx,
+                                                            float* __restrict__ val,
+                                                            const int* __restrict__ pre) {
+  extern __shared__ uint32_t dyn[];
+  topk_row<PRE>(p, S, row_len, k, map, idx, val, pre, blockIdx.x, blockIdx.y, dyn);
+}
+
+// Only the rows r with only[r] != 0 (rows another path could not finish).  Normally
+// there is none, so a small grid strides over the rows.
+__global__ __launch_bounds__(kTopkThreads) void topk_only_kernel(Prob p, const float* __restrict__ S,
+                                                                 int k, int* __restrict__ idx,
+                                                                 float* __restrict__ val,
+                                                                 const int* __restrict__ only) {
+  extern __shared__ uint32_t dyn[];
+  const int rows = p.n_seq * p.n_q;
+  for (int r = blockIdx.x; r < rows; r += gridDim.x) {
+    if (!only[r]) continue;
+    topk_row<false>(p, S, p.L, k, nullptr, idx, val, nullptr, r % p.n_q, r / p.n_q, dyn);
+    __syncthreads();
+  }
+}
+
 __global__ void zero_ints_kernel(int* __restrict__ pre, int stride, int count) {
   // clears the histogram and the two list counters of one row per blockIdx.y
   int* g = pre + (size_t)blockIdx.y * stride;
@@ -405,11 +393,14 @@ size_t topk_ws_bytes(const Prob& p, int k) {
   return (size_t)p.n_seq * p.n_q * stride * sizeof(int);
 }
 
-template <bool PRE>
+template <int WHICH>  // 0: topk_kernel<false>, 1: topk_kernel<true>, 2: topk_only_kernel
 static hipError_t set_lds_limit(size_t lds) {
   static size_t attr_bytes = 48 * 1024;  // default dynamic LDS limit
   if (lds > attr_bytes) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(topk_kernel<PRE>),
+    const void* f = WHICH == 0 ? reinterpret_cast<const void*>(topk_kernel<false>)
+                  : WHICH == 1 ? reinterpret_cast<const void*>(topk_kernel<true>)
+                               : reinterpret_cast<const void*>(topk_only_kernel);
+    hipError_t e = hipFuncSetAttribute(f,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_bytes = lds;
@@ -418,11 +409,18 @@ static hipError_t set_lds_limit(size_t lds) {
 }
 
 hipError_t launch_topk(const Prob& p, const float* S, int row_len, int k, const int* map, int* idx,
-                       float* val, void* ws, hipStream_t st) {
+                       float* val, void* ws, hipStream_t st, const int* only) {
   const size_t nwords = (size_t)(row_len + 31) / 32;
   const size_t second = nwords * 4 > (size_t)kCap * 8 ? nwords * 4 : (size_t)kCap * 8;
   const size_t lds = nwords * 4 + second;
   const dim3 grid(p.n_q, p.n_seq);
+  if (only) {
+    hipError_t e = set_lds_limit<2>(lds);
+    if (e != hipSuccess) return e;
+    const int rows = p.n_seq * p.n_q;
+    topk_only_kernel<<<rows < 256 ? rows : 256, kTopkThreads, lds, st>>>(p, S, k, idx, val, only);
+    return hipGetLastError();
+  }
   if (!map && use_split(p)) {
     int* pre = static_cast<int*>(ws);
     const int stride = (kPreHeader + k + 2 * kCap + 63) & ~63;
@@ -431,12 +429,12 @@ hipError_t launch_topk(const Prob& p, const float* S, int row_len, int k, const 
     const dim3 g2((p.L + kChunk - 1) / kChunk, p.n_q, p.n_seq);
     topk_hist_kernel<<<g2, kTopkThreads, 0, st>>>(p, S, k, pre);
     topk_partition_kernel<<<g2, kTopkThreads, 0, st>>>(p, S, k, pre);
-    hipError_t e = set_lds_limit<true>(lds);
+    hipError_t e = set_lds_limit<1>(lds);
     if (e != hipSuccess) return e;
     topk_kernel<true><<<grid, kTopkThreads, lds, st>>>(p, S, row_len, k, map, idx, val, pre);
     return hipGetLastError();
   }
-  hipError_t e = set_lds_limit<false>(lds);
+  hipError_t e = set_lds_limit<0>(lds);
   if (e != hipSuccess) return e;
   topk_kernel<false><<<grid, kTopkThreads, lds, st>>>(p, S, row_len, k, map, idx, val, nullptr);
   return hipGetLastError();

@@ -23,7 +23,7 @@ lib = ctypes.CDLL(LIB_PATH)
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
 DTYPE_CODES = {"f32": F32, "bf16": BF16, "e4m3": FP8_E4M3}
-OP_POOL, OP_ROUTE, OP_SCORE, OP_TOPK, OP_RERANK = range(5)
+OP_POOL, OP_ROUTE, OP_SCORE, OP_TOPK, OP_RERANK, OP_SELECT = range(6)
 STATUS_NAMES = {0: "MISA_OK", 1: "MISA_ERR_INVALID_ARG", 2: "MISA_ERR_UNSUPPORTED",
                 3: "MISA_ERR_WORKSPACE", 4: "MISA_ERR_HIP"}
 
@@ -49,6 +49,10 @@ lib.misa_score_tokens.restype = ctypes.c_int
 lib.misa_score_tokens.argtypes = [_P, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]
 lib.misa_topk.restype = ctypes.c_int
 lib.misa_topk.argtypes = [_P, _V, ctypes.c_int32, _V, _V, _V, ctypes.c_size_t, _V]
+lib.misa_select_tokens.restype = ctypes.c_int
+lib.misa_select_tokens.argtypes = [_P, _V, _V, _V, _V, _V, ctypes.c_int32, _V, _V, _V, ctypes.c_size_t, _V]
+lib.misa_select_row_flags_offset.restype = ctypes.c_int64
+lib.misa_select_row_flags_offset.argtypes = [_P, ctypes.c_int32, ctypes.c_int32]
 lib.misa_rerank.restype = ctypes.c_int
 lib.misa_rerank.argtypes = [_P, _V, _V, _V, _V, _V, ctypes.c_int32, ctypes.c_int32, _V, _V, _V,
                             ctypes.c_size_t, _V]
@@ -147,6 +151,22 @@ def topk(p: Problem, S, k: int, idx, val=None, ws=None) -> None:
     _check(lib.misa_topk(ctypes.byref(p.c()), _ptr(S), k, _ptr(idx), _ptr(val), w, wb, _stream()))
 
 
+def select_tokens(p: Problem, Q, W, heads, K, kscale, k: int, idx, val=None, ws=None) -> None:
+    w, wb = _ws(ws)
+    _check(lib.misa_select_tokens(ctypes.byref(p.c()), _ptr(Q), _ptr(W), _ptr(heads), _ptr(K), _ptr(kscale),
+                                  k, _ptr(idx), _ptr(val), w, wb, _stream()))
+
+
+def select_repaired_rows(p: Problem, routed: bool, k: int, ws) -> Optional[torch.Tensor]:
+    """Flags [n_seq, n_q] of the rows the last select_tokens call on `ws` recomputed by the
+    two-call path, or None when the problem does not take the sampled route."""
+    off = lib.misa_select_row_flags_offset(ctypes.byref(p.c()), int(routed), k)
+    if off < 0:
+        return None
+    n = p.n_seq * p.n_q
+    return ws[off:off + 4 * n].view(torch.int32).view(p.n_seq, p.n_q)
+
+
 def rerank(p: Problem, Q, W, K, kscale, cand, k_cand: int, k: int, idx, val=None, ws=None) -> None:
     w, wb = _ws(ws)
     _check(lib.misa_rerank(ctypes.byref(p.c()), _ptr(Q), _ptr(W), _ptr(K), _ptr(kscale), _ptr(cand),
@@ -181,13 +201,15 @@ def to_device(inp: dict, device="cuda") -> dict:
 class Indexer:
     """Preallocated outputs + workspaces for one problem; runs the stages in order."""
 
-    def __init__(self, p: Problem, k: int, k_cand: int = 0, device="cuda", want_E=False, want_val=False):
-        self.p, self.k, self.k_cand = p, k, k_cand
+    def __init__(self, p: Problem, k: int, k_cand: int = 0, device="cuda", want_E=False, want_val=False,
+                 fused=False):
+        """fused: stages 3 and 4 run as one select_tokens call and no score matrix is kept."""
+        self.p, self.k, self.k_cand, self.fused = p, k, k_cand, fused
         rows = (p.n_seq, p.n_q)
         self.Kp = torch.empty((p.n_seq, p.M, p.d), dtype=torch.float32, device=device)
         self.heads = torch.empty(rows + (p.h,), dtype=torch.int32, device=device)
         self.E = torch.empty(rows + (p.H,), dtype=torch.float32, device=device) if want_E else None
-        self.S = torch.empty(rows + (p.L,), dtype=torch.float32, device=device)
+        self.S = None if fused else torch.empty(rows + (p.L,), dtype=torch.float32, device=device)
         k1 = k_cand if k_cand else k
         self.idx1 = torch.empty(rows + (k1,), dtype=torch.int32, device=device)
         self.val1 = torch.empty(rows + (k1,), dtype=torch.float32, device=device) if want_val else None
@@ -198,7 +220,9 @@ class Indexer:
             self.val = torch.empty(rows + (k,), dtype=torch.float32, device=device) if want_val else None
         self.ws = {op: alloc_workspace(p, op, k1 if op == OP_TOPK else k_cand, device)
                    for op in (OP_POOL, OP_ROUTE, OP_SCORE, OP_TOPK, OP_RERANK)
-                   if op != OP_RERANK or k_cand}
+                   if (op != OP_RERANK or k_cand) and not (fused and op == OP_TOPK)}
+        if fused:
+            self.ws[OP_SELECT] = alloc_workspace(p, OP_SELECT, k1, device)
 
     def pool(self, K, kscale):
         pool_keys(self.p, K, kscale, self.Kp, self.ws[OP_POOL])
@@ -213,6 +237,10 @@ class Indexer:
         topk(self.p, self.S, self.k_cand if self.k_cand else self.k, self.idx1, self.val1,
              self.ws[OP_TOPK])
 
+    def select_fused(self, Q, W, K, kscale, dense=False):
+        select_tokens(self.p, Q, W, None if dense else self.heads, K, kscale,
+                      self.k_cand if self.k_cand else self.k, self.idx1, self.val1, self.ws[OP_SELECT])
+
     def refine(self, Q, W, K, kscale):
         rerank(self.p, Q, W, K, kscale, self.idx1, self.k_cand, self.k, self.idx, self.val,
                self.ws[OP_RERANK])
@@ -222,8 +250,11 @@ class Indexer:
         if pool:
             self.pool(K, kscale)
         self.route(Q, W, K, kscale)
-        self.score(Q, W, K, kscale)
-        self.select()
+        if self.fused:
+            self.select_fused(Q, W, K, kscale)
+        else:
+            self.score(Q, W, K, kscale)
+            self.select()
         if self.k_cand:
             self.refine(Q, W, K, kscale)
         return self.idx

@@ -329,6 +329,7 @@ __device__ __forceinline__ void score_tile_body(
   __shared__ int nvis[QWG];
   __shared__ int s_head[QWG][HS];
   __shared__ int2 stg[FILTER ? 4 * NQL_ * kStageCap : 1];
+  __shared__ float s_tau[FILTER ? QWG : 1];  // thresholds of the workgroup's queries (+inf: no such query)
 
   const int LT = SAMPLE ? p.L / kSampleStride : p.L;  // keys in tile space
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -342,6 +343,7 @@ __device__ __forceinline__ void score_tile_body(
   for (int i = tid; i < QWG; i += 256) {
     const int n = q_base + i < p.n_q ? visible(p, seq, q_base + i) : 0;
     nvis[i] = SAMPLE ? n / kSampleStride : n;
+    if (FILTER) s_tau[i] = q_base + i < p.n_q ? aux.tau[(size_t)seq * p.n_q + q_base + i] : INFINITY;
   }
   for (int i = tid; i < QWG * HS; i += 256) {
     const int qi = i / HS, slot = i % HS, q = q_base + qi;
@@ -434,9 +436,8 @@ __device__ __forceinline__ void score_tile_body(
   float* s_tile = S + ((size_t)seq * p.n_q + q_base) * LT;
   int qn[NQL];
   uint32_t qoff[NQL];
-  // filter mode: thresholds of this lane's queries and the lengths of the wavefront's
-  // staging lists (wavefront-uniform, so they live in scalar registers)
-  float tauv[NQL];
+  // filter mode: the lengths of the wavefront's staging lists (wavefront-uniform, so they
+  // live in scalar registers); the thresholds are read from LDS where they are used
   int cnt[NQL];
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   int n_min = 0x7FFFFFFF;
@@ -447,8 +448,6 @@ __device__ __forceinline__ void score_tile_body(
     qn[j] = ok ? nvis[qi] : -1;   // -1: query does not exist, nothing is stored
     qoff[j] = (uint32_t)qi * (uint32_t)LT;
     cnt[j] = 0;
-    tauv[j] = INFINITY;
-    if (FILTER && ok) tauv[j] = aux.tau[(size_t)seq * p.n_q + q_base + qi];
   }
   // Moves staging list j (the candidates of the two queries in accumulator slot j of the
   // lower and of the upper half-wave) to the global lists of those queries.
@@ -491,17 +490,16 @@ __device__ __forceinline__ void score_tile_body(
   // workgroup, all of which exist: no masks are needed there
   const int plain_end = min(n_min, k_end);
 
-  // LDS fragment positions of this lane (16-byte units): row col of column tile 0,
-  // chunk (2 ks + hf) XOR-swizzled by the row; the other tile is 32 rows further.
-  int frag[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) frag[ks] = col * 16 + ((ks * 2 + hf) ^ (col & 15));
-
+  // LDS fragment positions of this lane (16-byte units): row col of column tile 0, chunk
+  // (2 ks + hf) XOR-swizzled by the row, i.e. frag0 ^ (2 ks); the other column tile is 32
+  // rows further.  Only frag0 is kept; the XOR is applied to frag0 + tile offset (whose low
+  // four bits are zero) at every use, which costs nothing and frees seven registers.
+  const int frag0 = col * 16 + (hf ^ (col & 15));
   // One 32-key column tile: eight fragment reads, 8 x RT MFMAs.
-  auto mfma_tile = [&](f32x16 (&acc)[RT], const uint4* tile, int ct) {
+  auto mfma_tile = [&](f32x16 (&acc)[RT], int tile) {  // tile: buffer * 1024 + column tile * 512
     Frag b[8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) b[ks].u = tile[frag[ks] + ct * 512];
+    for (int ks = 0; ks < 8; ++ks) b[ks].u = (&ktile[0][0])[(frag0 + tile) ^ (2 * ks)];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
@@ -516,18 +514,13 @@ __device__ __forceinline__ void score_tile_body(
   };
   // ReLU, gate, head sum and store of one finished column tile.  PLAIN: every
   // query of the workgroup exists and sees the whole tile, so nothing is masked.
-  auto epilogue = [&](auto plain_tag, const f32x16 (&acc)[RT], int key, float scale) {
+  // the gated ReLU of accumulator register r of row tile rt, added to its query's sum
+  auto head_term = [&](float (&out)[NQL], const f32x16 (&acc)[RT], int rt, int r) {
+    const int j = HS == 8 ? rt * 2 + (r >> 3) : (HS == 16 ? rt : 0);
+    out[j] = fmaf(gate[rt][r], relu(acc[rt][r]), out[j]);
+  };
+  auto finish = [&](auto plain_tag, float (&out)[NQL], int key, float scale) {
     constexpr bool PLAIN = decltype(plain_tag)::value;
-    float out[NQL];
-#pragma unroll
-    for (int j = 0; j < NQL; ++j) out[j] = 0.f;
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = HS == 8 ? rt * 2 + (r >> 3) : (HS == 16 ? rt : 0);
-        out[j] = fmaf(gate[rt][r], relu(acc[rt][r]), out[j]);
-      }
     if (KDT == MISA_FP8_E4M3) {
 #pragma unroll
       for (int j = 0; j < NQL; ++j) out[j] *= scale;
@@ -535,7 +528,8 @@ __device__ __forceinline__ void score_tile_body(
     if (FILTER) {
 #pragma unroll
       for (int j = 0; j < NQL; ++j) {
-        const bool pass = out[j] >= tauv[j] && (PLAIN || (key < k_end && key < qn[j]));
+        const float tau = s_tau[wave * QW + (HS == 8 ? (j >> 1) * 4 + hf * 2 + (j & 1) : (HS == 16 ? j * 2 + hf : hf))];
+        const bool pass = out[j] >= tau && (PLAIN || (key < k_end && key < qn[j]));
         const unsigned long long m = __ballot(pass);
         // list length + passing lanes below this one
         const int slot = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, cnt[j]));
@@ -552,24 +546,50 @@ __device__ __forceinline__ void score_tile_body(
         if (key < k_end && qn[j] >= 0) s_tile[qoff[j] + (uint32_t)key] = key < qn[j] ? out[j] : -INFINITY;
     }
   };
+  auto epilogue = [&](auto plain_tag, const f32x16 (&acc)[RT], int key, float scale) {
+    float out[NQL];
+#pragma unroll
+    for (int j = 0; j < NQL; ++j) out[j] = 0.f;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) head_term(out, acc, rt, r);
+    finish(plain_tag, out, key, scale);
+  };
+  // The matrix instructions of column tile ct into acc_new, each followed by its share
+  // (two accumulator registers) of the head sums of the previous column tile acc_old;
+  // scheduling barriers pin that order, so a wavefront feeds both pipes at once.
+  auto tile_step = [&](auto plain_tag, f32x16 (&acc_new)[RT], int tile,
+                       const f32x16 (&acc_old)[RT], int key, float scale) {
+    Frag b[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) b[ks].u = (&ktile[0][0])[(frag0 + tile) ^ (2 * ks)];
+    float out[NQL];
+#pragma unroll
+    for (int j = 0; j < NQL; ++j) out[j] = 0.f;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        if (ks == 0) {
+          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          acc_new[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b[ks].v, zero, 0, 0, 0);
+        } else {
+          acc_new[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b[ks].v, acc_new[rt], 0, 0, 0);
+        }
+        const int e = (ks * RT + rt) * 2;   // 8 RT steps x 2 = the 16 RT accumulator registers
+        head_term(out, acc_old, e / 16, e % 16);
+        head_term(out, acc_old, (e + 1) / 16, (e + 1) % 16);
+        // an empty volatile statement on the running sum keeps these operations between
+        // the two scheduling barriers (plain arithmetic would be free to move past them)
+        asm volatile("" : "+v"(out[HS == 8 ? (e / 16) * 2 + ((e % 16) >> 3) : (HS == 16 ? e / 16 : 0)]));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    finish(plain_tag, out, key, scale);
+  };
   using Yes = std::true_type;
   using No = std::false_type;
-  // Scheduling request for a block that holds the MFMAs of one column tile and the
-  // epilogue of the previous one: fragment reads first, then one MFMA followed by
-  // a share of the vector instructions, repeated, so that both pipes stay busy.
-  auto interleave = [&]() {
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);        // DS reads
-#pragma unroll
-    for (int i = 0; i < 8 * RT; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
-      __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);     // ten VALU
-      if (FILTER) {
-        __builtin_amdgcn_sched_group_barrier(0x004, 2, 0);    // ballot bookkeeping
-        if (i % 4 == 3) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // a staged candidate write
-      }
-    }
-  };
-
   // The column tiles of the key range form one stream; the MFMAs of a tile are
   // issued together with the epilogue of the tile before it (two accumulator
   // sets), so matrix and vector pipes overlap inside a wavefront.  Per 64-key
@@ -587,22 +607,18 @@ __device__ __forceinline__ void score_tile_body(
     if (n_tiles > 1) MISA_TILE_LOAD(k_begin + kKT);
     f32x16 accA[RT], accB[RT];
     float scaleA = 1.f, scaleB = 1.f;
-    mfma_tile(accA, ktile[0], 0);
+    mfma_tile(accA, 0);
     if (KDT == MISA_FP8_E4M3) scaleA = kscl[0][col];
     auto body = [&](auto tag, int i) {
       const int buf = i & 1, k0 = k_begin + i * kKT;
       const bool more = i + 1 < n_tiles;
-      mfma_tile(accB, ktile[buf], 1);
-      epilogue(tag, accA, k0 + col, scaleA);
-      interleave();
+      tile_step(tag, accB, buf * 1024 + 512, accA, k0 + col, scaleA);
       if (KDT == MISA_FP8_E4M3) scaleB = kscl[buf][32 + col];
       if (more) MISA_TILE_STORE(buf ^ 1);
       __syncthreads();
       if (more) {
         if (i + 2 < n_tiles) MISA_TILE_LOAD(k0 + 2 * kKT);
-        mfma_tile(accA, ktile[buf ^ 1], 0);
-        epilogue(tag, accB, k0 + 32 + col, scaleB);
-        interleave();
+        tile_step(tag, accA, (buf ^ 1) * 1024, accB, k0 + 32 + col, scaleB);
         if (KDT == MISA_FP8_E4M3) scaleA = kscl[buf ^ 1][col];
       } else {
         epilogue(tag, accB, k0 + 32 + col, scaleB);
@@ -635,8 +651,11 @@ __device__ __forceinline__ void score_tile_body(
   }
 }
 
+// Two wavefronts per SIMD (at most 256 vector registers) except for 64 head slots, whose
+// four row tiles need the whole register file.
 template <int KDT, int HS, int MODE>
-__global__ __launch_bounds__(256) void score_tile_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HS == 64 ? 1 : 2, HS == 64 ? 1 : 2)))
+void score_tile_kernel(
     Prob p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
     float* __restrict__ S, TileAux aux) {

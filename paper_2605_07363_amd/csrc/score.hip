@@ -436,8 +436,9 @@ __device__ __forceinline__ void score_tile_body(
   float* s_tile = S + ((size_t)seq * p.n_q + q_base) * LT;
   int qn[NQL];
   uint32_t qoff[NQL];
-  // filter mode: the lengths of the wavefront's staging lists (wavefront-uniform, so they
-  // live in scalar registers); the thresholds are read from LDS where they are used
+  // filter mode: thresholds of this lane's queries and the lengths of the wavefront's
+  // staging lists (wavefront-uniform, so they live in scalar registers)
+  float tauv[NQL];
   int cnt[NQL];
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   int n_min = 0x7FFFFFFF;
@@ -448,6 +449,7 @@ __device__ __forceinline__ void score_tile_body(
     qn[j] = ok ? nvis[qi] : -1;   // -1: query does not exist, nothing is stored
     qoff[j] = (uint32_t)qi * (uint32_t)LT;
     cnt[j] = 0;
+    tauv[j] = FILTER ? s_tau[qi] : 0.f;
   }
   // Moves staging list j (the candidates of the two queries in accumulator slot j of the
   // lower and of the upper half-wave) to the global lists of those queries.
@@ -455,32 +457,32 @@ __device__ __forceinline__ void score_tile_body(
     const int c = cnt[j];
     const int2* src = stg + (wave_u * NQL + j) * kStageCap;
     // entries of each query: first the totals, then one atomic per query reserves the room
-    int tot[2] = {0, 0};
+    int tot0 = 0, tot1 = 0;
     for (int i0 = 0; i0 < c; i0 += 64) {
       const bool in = i0 + lane < c;
       const bool up = in && src[min(i0 + lane, c - 1)].x < 0;
       const int n_up = __popcll(__ballot(up));
-      tot[1] += n_up;
-      tot[0] += min(64, c - i0) - n_up;
+      tot1 += n_up;
+      tot0 += min(64, c - i0) - n_up;
     }
     const int qi = wave_u * QW + (HS == 8 ? (j >> 1) * 4 + (lane & 1) * 2 + (j & 1) : (HS == 16 ? j * 2 + (lane & 1) : (lane & 1)));
     const size_t my_row = (size_t)seq * p.n_q + q_base + qi;   // lanes 0 and 1: the two queries
     int base = 0;
-    const int mine = lane == 0 ? tot[0] : tot[1];
+    const int mine = lane == 0 ? tot0 : tot1;
     if (lane < 2 && mine > 0) base = atomicAdd(&aux.count[my_row], mine);
-    int run[2] = {__shfl(base, 0), __shfl(base, 1)};
+    int run0 = __shfl(base, 0), run1 = __shfl(base, 1);
     const long long row0 = __shfl((long long)my_row, 0), row1 = __shfl((long long)my_row, 1);
     for (int i0 = 0; i0 < c; i0 += 64) {
       const bool in = i0 + lane < c;
       int2 e = src[min(i0 + lane, c - 1)];
       const bool up = in && e.x < 0, down = in && e.x >= 0;
       const unsigned long long mu = __ballot(up), md = __ballot(down);
-      const int pos = up ? run[1] + __popcll(mu & ((1ull << lane) - 1ull))
-                         : run[0] + __popcll(md & ((1ull << lane) - 1ull));
+      const int pos = up ? run1 + __popcll(mu & ((1ull << lane) - 1ull))
+                         : run0 + __popcll(md & ((1ull << lane) - 1ull));
       e.x &= 0x7FFFFFFF;
       if (in && pos < aux.cap) aux.cand[(up ? row1 : row0) * aux.cap + pos] = e;
-      run[1] += __popcll(mu);
-      run[0] += __popcll(md);
+      run1 += __popcll(mu);
+      run0 += __popcll(md);
     }
     cnt[j] = 0;
   };
@@ -528,8 +530,7 @@ __device__ __forceinline__ void score_tile_body(
     if (FILTER) {
 #pragma unroll
       for (int j = 0; j < NQL; ++j) {
-        const float tau = s_tau[wave * QW + (HS == 8 ? (j >> 1) * 4 + hf * 2 + (j & 1) : (HS == 16 ? j * 2 + hf : hf))];
-        const bool pass = out[j] >= tau && (PLAIN || (key < k_end && key < qn[j]));
+        const bool pass = out[j] >= tauv[j] && (PLAIN || (key < k_end && key < qn[j]));
         const unsigned long long m = __ballot(pass);
         // list length + passing lanes below this one
         const int slot = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, cnt[j]));
@@ -588,6 +589,22 @@ __device__ __forceinline__ void score_tile_body(
       }
     finish(plain_tag, out, key, scale);
   };
+  // Filter mode leaves the order inside a step to the compiler's scheduler (its compare /
+  // ballot / staged-write tail does not fit the fixed pattern and measured slower with it),
+  // with a request to spread the vector work between the matrix instructions.
+  auto loose_step = [&](auto plain_tag, f32x16 (&acc_new)[RT], int tile, const f32x16 (&acc_old)[RT],
+                        int key, float scale) {
+    mfma_tile(acc_new, tile);
+    epilogue(plain_tag, acc_old, key, scale);
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);        // DS reads
+#pragma unroll
+    for (int i = 0; i < 8 * RT; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);     // ten VALU
+      __builtin_amdgcn_sched_group_barrier(0x004, 2, 0);      // ballot bookkeeping
+      if (i % 4 == 3) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // a staged candidate write
+    }
+  };
   using Yes = std::true_type;
   using No = std::false_type;
   // The column tiles of the key range form one stream; the MFMAs of a tile are
@@ -612,13 +629,15 @@ __device__ __forceinline__ void score_tile_body(
     auto body = [&](auto tag, int i) {
       const int buf = i & 1, k0 = k_begin + i * kKT;
       const bool more = i + 1 < n_tiles;
-      tile_step(tag, accB, buf * 1024 + 512, accA, k0 + col, scaleA);
+      if (FILTER) loose_step(tag, accB, buf * 1024 + 512, accA, k0 + col, scaleA);
+      else tile_step(tag, accB, buf * 1024 + 512, accA, k0 + col, scaleA);
       if (KDT == MISA_FP8_E4M3) scaleB = kscl[buf][32 + col];
       if (more) MISA_TILE_STORE(buf ^ 1);
       __syncthreads();
       if (more) {
         if (i + 2 < n_tiles) MISA_TILE_LOAD(k0 + 2 * kKT);
-        tile_step(tag, accA, (buf ^ 1) * 1024, accB, k0 + 32 + col, scaleB);
+        if (FILTER) loose_step(tag, accA, (buf ^ 1) * 1024, accB, k0 + 32 + col, scaleB);
+        else tile_step(tag, accA, (buf ^ 1) * 1024, accB, k0 + 32 + col, scaleB);
         if (KDT == MISA_FP8_E4M3) scaleA = kscl[buf ^ 1][col];
       } else {
         epilogue(tag, accB, k0 + 32 + col, scaleB);

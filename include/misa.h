@@ -78,6 +78,13 @@ typedef enum misa_op {
   MISA_OP_SELECT = 5
 } misa_op;
 
+/* Router scores of the routing-score ablation (appendix "Ablation: routing score"). */
+typedef enum misa_router_score {
+  MISA_ROUTER_BLOCK_POOLED = 0, /* the method's own score: misa_route_heads                 */
+  MISA_ROUTER_GATE = 1,         /* variant (a): E_j = w_j, the gating weight as it is       */
+  MISA_ROUTER_QUERY_NORM = 2    /* variant (b): E_j = ||q_j||_2                             */
+} misa_router_score;
+
 /* Problem description shared by all calls (host struct, passed by pointer). */
 typedef struct misa_problem {
   int32_t n_seq;          /* sequences in the batch, >= 1                             */
@@ -139,6 +146,19 @@ misa_status misa_pool_keys(const misa_problem* p, const void* K, const float* ks
 misa_status misa_route_heads(const misa_problem* p, const void* Q, const float* W,
                              const float* Kp, const void* K, const float* kscale,
                              int32_t* heads, float* E, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Head routing with one of the two content-free scores that the appendix
+ * "Ablation: routing score" compares the method with: kind MISA_ROUTER_GATE
+ * ranks the heads by their gate W[j] (signed, as printed there), kind
+ * MISA_ROUTER_QUERY_NORM by the Euclidean norm of Q[j].  Same selection rule
+ * and outputs as misa_route_heads (top-h, ties to the lower index, ascending);
+ * the keys are not consulted, no workspace is needed.
+ *   heads  out  [n_seq, n_q, h] int32
+ *   E      out  [n_seq, n_q, H] float or NULL
+ */
+misa_status misa_route_heads_proxy(const misa_problem* p, const void* Q, const float* W,
+                                   int32_t kind, int32_t* heads, float* E, void* stream);
 
 /*
  * Stage 3 - token scoring with the active heads (Eq. misa_score).

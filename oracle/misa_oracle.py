@@ -42,7 +42,7 @@ import numpy as np
 
 __all__ = [
     "e4m3fn_decode_table", "bf16_bits_to_f64", "dequantise",
-    "pool_keys", "route_affinity", "route_heads", "score_tokens", "dsa_scores",
+    "pool_keys", "route_affinity", "route_heads", "route_heads_proxy", "score_tokens", "dsa_scores",
     "topk", "rerank", "misa", "misa_dagger", "dsa_dense", "iou", "recall",
     "head_token_products",
 ]
@@ -164,6 +164,23 @@ def route_heads(q, w, K, B: int, h: int, n: int | None = None):
     else:
         A = route_affinity(q, w, Kp)
         E = np.abs(A).sum(axis=1) / float(M)
+    return _top_by_value_then_index(E, h), E
+
+
+def route_heads_proxy(q, w, h: int, kind: str):
+    """Head sets of the two content-free router scores of the appendix "Ablation: routing
+    score": kind 'gate' ranks heads by the gating weight w_j as it is, kind 'qnorm' by the
+    Euclidean norm of q_j.  Returns (heads ascending int64 [h], E float64 [H])."""
+    q = np.asarray(q, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    if not 1 <= h <= q.shape[0]:
+        raise ValueError("h must be in 1..H")
+    if kind == "gate":
+        E = w.copy()
+    elif kind == "qnorm":
+        E = np.sqrt((q * q).sum(axis=1))
+    else:
+        raise ValueError("kind must be 'gate' or 'qnorm'")
     return _top_by_value_then_index(E, h), E
 
 

@@ -130,6 +130,19 @@ misa_status misa_route_heads(const misa_problem* p, const void* Q, const float* 
                     "misa_route_heads launch");
 }
 
+misa_status misa_route_heads_proxy(const misa_problem* p, const void* Q, const float* W, int32_t kind,
+                                   int32_t* heads, float* E, void* stream) {
+  misa::Prob pr;
+  misa_status st = check_problem(p, &pr);
+  if (st != MISA_OK) return st;
+  if ((st = check_queries(Q, W)) != MISA_OK) return st;
+  if (!heads) return fail(MISA_ERR_INVALID_ARG, "heads is NULL");
+  if (kind != MISA_ROUTER_GATE && kind != MISA_ROUTER_QUERY_NORM)
+    return fail(MISA_ERR_INVALID_ARG, "kind must be MISA_ROUTER_GATE or MISA_ROUTER_QUERY_NORM (got %d)", kind);
+  return hip_result(misa::launch_route_proxy(pr, p->q_dtype, kind, Q, W, heads, E, (hipStream_t)stream),
+                    "misa_route_heads_proxy launch");
+}
+
 misa_status misa_score_tokens(const misa_problem* p, const void* Q, const float* W,
                               const int32_t* heads, const void* K, const float* kscale, float* S,
                               void* ws, size_t ws_bytes, void* stream) {

@@ -16,6 +16,9 @@ hipError_t launch_route(const Prob& p, int k_dtype, int q_dtype, const void* Q, 
                         const float* Kp, const void* K, const float* kscale, int* heads, float* E,
                         void* ws, hipStream_t st);
 
+hipError_t launch_route_proxy(const Prob& p, int q_dtype, int kind, const void* Q, const float* W,
+                              int* heads, float* E, hipStream_t st);
+
 // Scores of all L keys (cand == nullptr, out = S [n_seq, n_q, L]) or of the
 // k_cand listed candidates (out = [n_seq, n_q, k_cand]).
 hipError_t launch_score(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,

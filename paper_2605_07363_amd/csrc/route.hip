@@ -318,6 +318,62 @@ __global__ __launch_bounds__(128) void route_finalize_kernel(
   }
 }
 
+// Content-free router scores of the routing-score ablation (appendix "Ablation: routing
+// score"): kind 1: E_j = w_j, the gate itself; kind 2: E_j = ||q_j||_2.  Same top-h rule.
+// One wavefront per query, lane = head.
+template <int QDT>
+__global__ __launch_bounds__(64) void route_proxy_kernel(Prob p, int kind, const void* __restrict__ Q,
+                                                         const float* __restrict__ W,
+                                                         int* __restrict__ heads,
+                                                         float* __restrict__ E) {
+  __shared__ float Es[kWave];
+  __shared__ int sel[kWave];
+  const int t = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
+  const size_t qi = ((size_t)seq * p.n_q + t) * p.H + tid;
+  float e = -INFINITY;
+  if (tid < p.H) {
+    if (kind == MISA_ROUTER_GATE) {
+      e = W[qi];
+    } else {
+      float qv[kD];
+      load_query_head<QDT>(Q, qi, qv);
+      float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+      for (int c = 0; c < kD; c += 4) {
+        s0 = fmaf(qv[c], qv[c], s0);
+        s1 = fmaf(qv[c + 1], qv[c + 1], s1);
+        s2 = fmaf(qv[c + 2], qv[c + 2], s2);
+        s3 = fmaf(qv[c + 3], qv[c + 3], s3);
+      }
+      e = sqrtf((s0 + s1) + (s2 + s3));
+    }
+    if (E) E[qi] = e;
+  }
+  if (e == 0.f) e = 0.f;  // -0.0 ties with +0.0
+  Es[tid] = e;
+  __syncthreads();
+  int rank = 0;
+  for (int i = 0; i < p.H; ++i) {
+    const float o = Es[i];
+    rank += (o > e || (o == e && i < tid)) ? 1 : 0;
+  }
+  sel[tid] = (tid < p.H && rank < p.h) ? 1 : 0;
+  __syncthreads();
+  if (sel[tid]) {
+    int pos = 0;
+    for (int i = 0; i < tid; ++i) pos += sel[i];
+    heads[((size_t)seq * p.n_q + t) * p.h + pos] = tid;
+  }
+}
+
+hipError_t launch_route_proxy(const Prob& p, int q_dtype, int kind, const void* Q, const float* W,
+                              int* heads, float* E, hipStream_t st) {
+  const dim3 grid(p.n_q, p.n_seq);
+  if (q_dtype == MISA_F32) route_proxy_kernel<MISA_F32><<<grid, 64, 0, st>>>(p, kind, Q, W, heads, E);
+  else route_proxy_kernel<MISA_BF16><<<grid, 64, 0, st>>>(p, kind, Q, W, heads, E);
+  return hipGetLastError();
+}
+
 // Row groups (of 64 query-head rows) per workgroup of the tiled kernel.
 static int route_row_groups(const Prob& p) {
   const long long groups = ((long long)p.n_q * p.H + 63) / 64;

@@ -45,6 +45,8 @@ lib.misa_pool_keys.restype = ctypes.c_int
 lib.misa_pool_keys.argtypes = [_P, _V, _V, _V, _V, ctypes.c_size_t, _V]
 lib.misa_route_heads.restype = ctypes.c_int
 lib.misa_route_heads.argtypes = [_P, _V, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]
+lib.misa_route_heads_proxy.restype = ctypes.c_int
+lib.misa_route_heads_proxy.argtypes = [_P, _V, _V, ctypes.c_int32, _V, _V, _V]
 lib.misa_score_tokens.restype = ctypes.c_int
 lib.misa_score_tokens.argtypes = [_P, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]
 lib.misa_topk.restype = ctypes.c_int
@@ -138,6 +140,14 @@ def route_heads(p: Problem, Q, W, Kp, K, kscale, heads, E=None, ws=None) -> None
     w, wb = _ws(ws)
     _check(lib.misa_route_heads(ctypes.byref(p.c()), _ptr(Q), _ptr(W), _ptr(Kp), _ptr(K), _ptr(kscale),
                                 _ptr(heads), _ptr(E), w, wb, _stream()))
+
+
+ROUTER_BLOCK_POOLED, ROUTER_GATE, ROUTER_QUERY_NORM = range(3)
+
+
+def route_heads_proxy(p: Problem, Q, W, kind: int, heads, E=None) -> None:
+    _check(lib.misa_route_heads_proxy(ctypes.byref(p.c()), _ptr(Q), _ptr(W), kind, _ptr(heads), _ptr(E),
+                                      _stream()))
 
 
 def score_tokens(p: Problem, Q, W, heads, K, kscale, S, ws=None) -> None:

@@ -7,7 +7,9 @@ hyper-parameters of the method; Experimental results, "Default MISA
 hyperparameters", and the ablations on B and h), once single-stage (MISA,
 Eq. misa_topk) and once with the dense re-rank of k' = 4k candidates (Eq.
 misa_final_topk), and reports which fraction of the dense all-head top-k set
-(Eq. dsa_topk) each selection recovers.  The inputs are the seeded synthetic
+(Eq. dsa_topk) each selection recovers; the same for the two content-free
+router scores of the appendix "Ablation: routing score" (gate alone, query
+norm).  The inputs are the seeded synthetic
 caches of workloads.py, so the figures describe those inputs, not a trained
 model.
 
@@ -72,9 +74,22 @@ def main() -> int:
             r2 = overlap(two.run(K, ks, Q, W).view(rows, -1), ref)
             out.append({"B": B, "h": h, "misa_recall": round(r1, 4), "misa_dagger_recall": round(r2, 4)})
             print(f"B={B:7d} h={h:3d}  MISA {r1:.4f}  MISA-dagger(k'=4k) {r2:.4f}", file=sys.stderr, flush=True)
+    # the two content-free router scores of the appendix "Ablation: routing score" (no block size)
+    proxy = []
+    for h in [int(x) for x in args.heads.split(",") if int(x) <= base.H]:
+        row = {"h": h}
+        for name, kind in (("gate", misa.ROUTER_GATE), ("query_norm", misa.ROUTER_QUERY_NORM)):
+            ix = misa.Indexer(problem(h, base.B), base.k)
+            misa.route_heads_proxy(ix.p, Q, W, kind, ix.heads)
+            ix.score(Q, W, K, ks)
+            ix.select()
+            row[name + "_recall"] = round(overlap(ix.idx.view(rows, -1), ref), 4)
+        proxy.append(row)
+        print(f"router ablation h={h:3d}  gate {row['gate_recall']:.4f}  query norm {row['query_norm_recall']:.4f}",
+              file=sys.stderr, flush=True)
     torch.cuda.synchronize()
     print(json.dumps({"workload": base.name, "n_seq": base.n_seq, "L": base.L, "H": base.H, "k": base.k,
-                      "rows": out}))
+                      "rows": out, "router_ablation": proxy}))
     return 0
 
 

@@ -121,6 +121,29 @@ def test_route_heads(misa, name, use_len):
     assert exact >= 0.9 * wl.n_seq * wl.n_q          # legal flips inside the margin must be rare
 
 
+@pytest.mark.parametrize("name", ["f32_decode", "bf16_decode", "bf16_prefill", "fp8_prefill_h32", "bf16_decode_H1"])
+@pytest.mark.parametrize("kind", ["gate", "qnorm"])
+def test_route_heads_proxy(misa, name, kind):
+    # content-free router scores of the routing-score ablation
+    wl = CASES[name]
+    inp = gen(name)
+    dv = misa.to_device(inp)
+    p = dv["problem"]
+    heads = torch.full((wl.n_seq, wl.n_q, wl.h), -5, dtype=torch.int32, device="cuda")
+    E = torch.empty((wl.n_seq, wl.n_q, wl.H), dtype=torch.float32, device="cuda")
+    code = misa.ROUTER_GATE if kind == "gate" else misa.ROUTER_QUERY_NORM
+    misa.route_heads_proxy(p, dv["Q"], dv["W"], code, heads, E)
+    heads, E = heads.cpu().numpy(), E.cpu().numpy()
+    for s in range(wl.n_seq):
+        for t in range(wl.n_q):
+            _, q, w, _ = oracle_view(inp, s, t)
+            ref_heads, ref_E = O.route_heads_proxy(q, w, wl.h, kind)
+            assert_scores_close(E[s, t], ref_E, f"proxy E {name} {kind} {s},{t}")
+            check_index_set(heads[s, t], ref_E, wl.h, f"proxy heads {name} {kind} {s},{t}")
+            if kind == "gate":                      # the gate is copied, so the set is exact
+                np.testing.assert_array_equal(heads[s, t], ref_heads)
+
+
 # --------------------------------------------------------------------- score
 @pytest.mark.parametrize("name", list(CASES))
 @pytest.mark.parametrize("use_len", [False, True])

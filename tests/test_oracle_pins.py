@@ -366,3 +366,32 @@ def test_cost_model_counts():
     c = O.head_token_products(131072, 64, 8, 64, 8192)
     assert c["misa"] == 1048576 + 131072 + 524288
     assert O.head_token_products(131072, 32, 8, 128)["dense"] / O.head_token_products(131072, 32, 8, 128)["misa"] == pytest.approx(3.878, abs=2e-3)
+
+
+# ---------------------------------------------------------------- router-score ablation variants
+def test_proxy_router_scores_closed_forms():
+    # Appendix "Ablation: routing score": (a) the gate alone, (b) the query norm.
+    rng = np.random.default_rng(41)
+    H, d, h = 12, 16, 5
+    q = rng.standard_normal((H, d))
+    w = rng.standard_normal(H)
+    heads, E = O.route_heads_proxy(q, w, h, "gate")
+    np.testing.assert_array_equal(E, w)
+    np.testing.assert_array_equal(heads, np.sort(np.argsort(-w)[:h]))          # distinct gates: plain sort
+    assert w[heads].min() > np.delete(w, heads).max()
+    # a negative gate of large magnitude is NOT up-weighted: it ranks last
+    w2 = w.copy(); w2[3] = -100.0
+    assert 3 not in O.route_heads_proxy(q, w2, H - 1, "gate")[0]
+    # (b): axis-aligned queries with known lengths; scaling a head by c scales its score by |c|
+    q3 = np.zeros((4, 3)); q3[0, 0] = 3.0; q3[1] = [1.0, 2.0, 2.0]; q3[2, 2] = -5.0; q3[3] = [0.0, 0.6, 0.8]
+    heads, E = O.route_heads_proxy(q3, np.ones(4), 2, "qnorm")
+    np.testing.assert_allclose(E, [3.0, 3.0, 5.0, 1.0], rtol=1e-15)
+    np.testing.assert_array_equal(heads, [0, 2])                              # tie 3.0 == 3.0 -> lower index
+    _, E2 = O.route_heads_proxy(-2.5 * q, w, h, "qnorm")
+    np.testing.assert_allclose(E2, 2.5 * O.route_heads_proxy(q, w, h, "qnorm")[1], rtol=1e-14)
+    np.testing.assert_allclose(O.route_heads_proxy(q, w, h, "qnorm")[1], np.linalg.norm(q, axis=1), rtol=1e-14)
+    # neither variant looks at the gates' sign convention of the main router or at the keys
+    with pytest.raises(ValueError):
+        O.route_heads_proxy(q, w, 0, "gate")
+    with pytest.raises(ValueError):
+        O.route_heads_proxy(q, w, h, "pooled")

@@ -83,6 +83,9 @@ def main() -> int:
     ap.add_argument("--active-heads", type=int, default=0, help="override the number of active heads h")
     ap.add_argument("--fused", action="store_true",
                     help="stages 3+4 as one misa_select_tokens call (no score matrix); prefill workloads")
+    ap.add_argument("--incremental-pool", action="store_true",
+                    help="decode workloads: the pooled keys of earlier tokens are kept and a step only re-pools "
+                         "the block of the newest token (misa_pool_keys_update), as a serving loop would")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate", type=int, default=3, help="key-cache copies rotated between steps (cold reads)")
     ap.add_argument("--no-graph", action="store_true",
@@ -120,13 +123,22 @@ def main() -> int:
         return 2
     ix = misa.Indexer(p, wl.k, wl.k_cand, fused=args.fused)
 
+    if args.incremental_pool and not wl.decode:
+        print("bench.py: --incremental-pool applies to the decode workloads (c0, c1, c3)", file=sys.stderr)
+        return 2
+    newest = torch.full((wl.n_seq,), wl.L - 1, dtype=torch.int32, device="cuda")
+    if args.incremental_pool:
+        for r in range(n_rot):                       # all copies hold the same keys: pool once
+            ix.pool(Ks[r], scales[r])
+
     stage_names = ["pool", "route"] + (["select"] if args.fused else ["score", "topk"]) + \
         (["rerank"] if wl.k_cand else [])
 
     def step(i, ev=None):
         K, ks = Ks[i % n_rot], scales[i % n_rot]
         mid = [lambda: ix.select_fused(Q, W, K, ks)] if args.fused else [lambda: ix.score(Q, W, K, ks), ix.select]
-        calls = [lambda: ix.pool(K, ks), lambda: ix.route(Q, W, K, ks)] + mid + \
+        pool = (lambda: ix.pool_update(K, ks, newest, 1)) if args.incremental_pool else (lambda: ix.pool(K, ks))
+        calls = [pool, lambda: ix.route(Q, W, K, ks)] + mid + \
             ([lambda: ix.refine(Q, W, K, ks)] if wl.k_cand else [])
         for j, c in enumerate(calls):
             if ev is not None:
@@ -219,7 +231,8 @@ def main() -> int:
 
     out = {
         "metric": "indexer query-key pairs/s (whole pass: pool+route+score+top-k" + ("+re-rank)" if wl.k_cand else ")")
-                  + (" [score+top-k fused]" if args.fused else ""),
+                  + (" [score+top-k fused]" if args.fused else "")
+                  + (" [pool: newest block only]" if args.incremental_pool else ""),
         "value": pairs / (dt / args.steps), "unit": "pairs/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32" if wl.k_dtype == "f32" else "bf16", "data": "synthetic",

@@ -128,6 +128,23 @@ misa_status misa_pool_keys(const misa_problem* p, const void* K, const float* ks
                            float* Kp, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Stage 1 after tokens were appended to the cache (Eq. pool on the blocks that
+ * changed): for every sequence i only the blocks from the one that holds token
+ * from_token[i] up to the last block of its current length len_i are
+ * recomputed, exactly as misa_pool_keys computes them; all other entries of
+ * Kp are left as they are.  With from_token[i] = the previous length this is
+ * the incremental maintenance of the pooled keys during decoding (normally one
+ * block per sequence).
+ *   from_token  in  [n_seq] int32 (device), clamped to 0..len_i
+ *   max_blocks  host-side bound on the number of blocks per sequence to update
+ *               (blocks beyond it are not recomputed), >= 1
+ *   ws          as for misa_pool_keys (MISA_OP_POOL)
+ */
+misa_status misa_pool_keys_update(const misa_problem* p, const void* K, const float* kscale,
+                                  float* Kp, const int32_t* from_token, int32_t max_blocks,
+                                  void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Stage 2 - head routing (Eq. misa_route_score, Eq. misa_route).
  * For every query:  A[j,b] = W[j] * ReLU(Q[j] . k~_b),
  *                   E[j]   = (1/M_n) * sum_b |A[j,b]|,   M_n = ceil(n / B),

@@ -115,6 +115,21 @@ misa_status misa_pool_keys(const misa_problem* p, const void* K, const float* ks
                     "misa_pool_keys launch");
 }
 
+misa_status misa_pool_keys_update(const misa_problem* p, const void* K, const float* kscale, float* Kp,
+                                  const int32_t* from_token, int32_t max_blocks, void* ws,
+                                  size_t ws_bytes, void* stream) {
+  misa::Prob pr;
+  misa_status st = check_problem(p, &pr);
+  if (st != MISA_OK) return st;
+  if ((st = check_keys(p, K, kscale)) != MISA_OK) return st;
+  if (!Kp || !from_token) return fail(MISA_ERR_INVALID_ARG, "Kp or from_token is NULL");
+  if (max_blocks < 1) return fail(MISA_ERR_INVALID_ARG, "max_blocks must be >= 1 (got %d)", max_blocks);
+  if ((st = check_ws(ws_bytes_for(pr, MISA_OP_POOL, 0), ws, ws_bytes)) != MISA_OK) return st;
+  return hip_result(misa::launch_pool(pr, p->k_dtype, K, kscale, Kp, ws, (hipStream_t)stream, from_token,
+                                      max_blocks),
+                    "misa_pool_keys_update launch");
+}
+
 misa_status misa_route_heads(const misa_problem* p, const void* Q, const float* W, const float* Kp,
                              const void* K, const float* kscale, int32_t* heads, float* E, void* ws,
                              size_t ws_bytes, void* stream) {

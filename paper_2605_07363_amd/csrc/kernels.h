@@ -7,8 +7,10 @@
 namespace misa {
 
 size_t pool_ws_bytes(const Prob& p);
+// from_token != nullptr: only the blocks from the one holding token from_token[seq] to the end
+// of each sequence are recomputed (at most max_blocks of them).
 hipError_t launch_pool(const Prob& p, int k_dtype, const void* K, const float* kscale, float* Kp,
-                       void* ws, hipStream_t st);
+                       void* ws, hipStream_t st, const int* from_token = nullptr, int max_blocks = 0);
 
 int route_splits(const Prob& p);
 size_t route_ws_bytes(const Prob& p);

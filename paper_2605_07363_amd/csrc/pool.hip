@@ -9,6 +9,8 @@
 // wavefront load instruction reads whole contiguous rows.  Each thread sums a
 // strided subset of rows in fp32; the subsets are combined through LDS in a
 // fixed order, so the result is deterministic.
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace misa {
@@ -18,8 +20,12 @@ constexpr int kPoolSplitFrom = 2048;  // blocks longer than this are sliced
 
 // slices == 1: Kp receives the block means.  slices > 1: blockIdx.x = block * slices + slice
 // and `Kp` is the workspace [n_seq, M, slices, 128] of partial SUMS.
+// from_token == nullptr: blockIdx.x / slices is the block.  Otherwise (update after tokens were
+// appended) it counts from the block that holds token from_token[seq], and blocks past the
+// sequence end are left alone.
 template <int DT>
-__global__ __launch_bounds__(256) void pool_kernel(Prob p, int slices, const void* __restrict__ K,
+__global__ __launch_bounds__(256) void pool_kernel(Prob p, int slices, const int* __restrict__ from_token,
+                                                   const void* __restrict__ K,
                                                    const float* __restrict__ kscale,
                                                    float* __restrict__ Kp) {
   using V = Vec16<DT>;
@@ -28,8 +34,13 @@ __global__ __launch_bounds__(256) void pool_kernel(Prob p, int slices, const voi
   constexpr int RPP = 256 / TPR;      // rows per pass of the workgroup
   __shared__ float red[RPP][kD];
 
-  const int b = blockIdx.x / slices, slice = blockIdx.x % slices, seq = blockIdx.y, tid = threadIdx.x;
+  const int slice = blockIdx.x % slices, seq = blockIdx.y, tid = threadIdx.x;
   const int len = seq_length(p, seq);
+  int b = blockIdx.x / slices;
+  if (from_token) {
+    b += min(max(from_token[seq], 0), len) / p.B;
+    if ((long long)b * p.B >= len) return;
+  }
   const long long blo = (long long)b * p.B;
   const long long bhi = min(blo + (long long)p.B, (long long)len);
   const long long lo = slices == 1 ? blo : blo + (long long)slice * kPoolSlice;
@@ -68,10 +79,17 @@ __global__ __launch_bounds__(256) void pool_kernel(Prob p, int slices, const voi
 // Adds the slice sums of every block in a fixed order (eight interleaved
 // subsets, then those in order) and divides by the token count.
 __global__ __launch_bounds__(1024) void pool_combine_kernel(Prob p, int slices,
+                                                            const int* __restrict__ from_token,
                                                             const float* __restrict__ part,
                                                             float* __restrict__ Kp) {
   __shared__ float red[8][kD];
-  const int b = blockIdx.x, seq = blockIdx.y, c = threadIdx.x % kD, g = threadIdx.x / kD;
+  const int seq = blockIdx.y, c = threadIdx.x % kD, g = threadIdx.x / kD;
+  int b = blockIdx.x;
+  if (from_token) {
+    const int len = seq_length(p, seq);
+    b += min(max(from_token[seq], 0), len) / p.B;
+    if ((long long)b * p.B >= len) return;
+  }
   const float* src = part + ((size_t)seq * p.M + b) * slices * kD + c;
   float s = 0.f;
 #pragma unroll 4
@@ -99,18 +117,19 @@ size_t pool_ws_bytes(const Prob& p) {
 }
 
 hipError_t launch_pool(const Prob& p, int k_dtype, const void* K, const float* kscale, float* Kp,
-                       void* ws, hipStream_t st) {
+                       void* ws, hipStream_t st, const int* from_token, int max_blocks) {
   const int sl = pool_slices(p);
-  const dim3 grid(p.M * sl, p.n_seq), block(256);
+  const int nb = from_token ? std::min(max_blocks, p.M) : p.M;
+  const dim3 grid(nb * sl, p.n_seq), block(256);
   float* dst = sl == 1 ? Kp : static_cast<float*>(ws);
   switch (k_dtype) {
-    case MISA_F32: pool_kernel<MISA_F32><<<grid, block, 0, st>>>(p, sl, K, kscale, dst); break;
-    case MISA_BF16: pool_kernel<MISA_BF16><<<grid, block, 0, st>>>(p, sl, K, kscale, dst); break;
-    default: pool_kernel<MISA_FP8_E4M3><<<grid, block, 0, st>>>(p, sl, K, kscale, dst); break;
+    case MISA_F32: pool_kernel<MISA_F32><<<grid, block, 0, st>>>(p, sl, from_token, K, kscale, dst); break;
+    case MISA_BF16: pool_kernel<MISA_BF16><<<grid, block, 0, st>>>(p, sl, from_token, K, kscale, dst); break;
+    default: pool_kernel<MISA_FP8_E4M3><<<grid, block, 0, st>>>(p, sl, from_token, K, kscale, dst); break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || sl == 1) return e;
-  pool_combine_kernel<<<dim3(p.M, p.n_seq), 1024, 0, st>>>(p, sl, dst, Kp);
+  pool_combine_kernel<<<dim3(nb, p.n_seq), 1024, 0, st>>>(p, sl, from_token, dst, Kp);
   return hipGetLastError();
 }
 

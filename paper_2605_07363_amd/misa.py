@@ -43,6 +43,8 @@ lib.misa_workspace_bytes.restype = ctypes.c_size_t
 lib.misa_workspace_bytes.argtypes = [_P, ctypes.c_int32, ctypes.c_int32]
 lib.misa_pool_keys.restype = ctypes.c_int
 lib.misa_pool_keys.argtypes = [_P, _V, _V, _V, _V, ctypes.c_size_t, _V]
+lib.misa_pool_keys_update.restype = ctypes.c_int
+lib.misa_pool_keys_update.argtypes = [_P, _V, _V, _V, _V, ctypes.c_int32, _V, ctypes.c_size_t, _V]
 lib.misa_route_heads.restype = ctypes.c_int
 lib.misa_route_heads.argtypes = [_P, _V, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]
 lib.misa_route_heads_proxy.restype = ctypes.c_int
@@ -134,6 +136,12 @@ def alloc_workspace(p: Problem, op: int, k: int = 0, device="cuda") -> Optional[
 def pool_keys(p: Problem, K, kscale, Kp, ws=None) -> None:
     w, wb = _ws(ws)
     _check(lib.misa_pool_keys(ctypes.byref(p.c()), _ptr(K), _ptr(kscale), _ptr(Kp), w, wb, _stream()))
+
+
+def pool_keys_update(p: Problem, K, kscale, Kp, from_token, max_blocks: int, ws=None) -> None:
+    w, wb = _ws(ws)
+    _check(lib.misa_pool_keys_update(ctypes.byref(p.c()), _ptr(K), _ptr(kscale), _ptr(Kp), _ptr(from_token),
+                                     max_blocks, w, wb, _stream()))
 
 
 def route_heads(p: Problem, Q, W, Kp, K, kscale, heads, E=None, ws=None) -> None:
@@ -236,6 +244,9 @@ class Indexer:
 
     def pool(self, K, kscale):
         pool_keys(self.p, K, kscale, self.Kp, self.ws[OP_POOL])
+
+    def pool_update(self, K, kscale, from_token, max_blocks=1):
+        pool_keys_update(self.p, K, kscale, self.Kp, from_token, max_blocks, self.ws[OP_POOL])
 
     def route(self, Q, W, K, kscale):
         route_heads(self.p, Q, W, self.Kp, K, kscale, self.heads, self.E, self.ws[OP_ROUTE])

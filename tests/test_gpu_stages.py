@@ -77,6 +77,43 @@ def test_pool_keys(misa, name, use_len):
         assert not got[s, ref.shape[0]:].any()          # blocks past the sequence end are zero
 
 
+@pytest.mark.parametrize("name", ["bf16_decode", "fp8_decode", "bf16_B4096"])
+def test_pool_keys_update_after_append(misa, name):
+    # Pooled keys maintained incrementally: pool at the old lengths, append tokens, update from the
+    # old lengths on -> identical to pooling everything at the new lengths; earlier blocks untouched.
+    wl = CASES[name]
+    rng = np.random.default_rng(17)
+    new_len = ragged(wl)
+    grow = rng.integers(0, 3 * wl.B + 2, wl.n_seq)
+    grow[0] = 1                                         # one decoded token
+    old_len = np.maximum(new_len - grow, 0).astype(np.int32)
+    inp = gen(name, new_len)
+    dv = misa.to_device(inp)
+    p_new = dv["problem"]
+    ws = misa.alloc_workspace(p_new, misa.OP_POOL)
+    full = torch.full((wl.n_seq, p_new.M, wl.d), 7.0, dtype=torch.float32, device="cuda")
+    misa.pool_keys(p_new, dv["K"], dv["kscale"], full, ws)
+    from dataclasses import replace
+    old_dev = torch.from_numpy(old_len).cuda()
+    p_old = replace(p_new, seq_len=old_dev)
+    Kp = torch.full_like(full, 7.0)
+    misa.pool_keys(p_old, dv["K"], dv["kscale"], Kp, ws)
+    stale = Kp.clone()
+    misa.pool_keys_update(p_new, dv["K"], dv["kscale"], Kp, old_dev, 5, ws)
+    assert torch.equal(Kp, full)
+    for s in range(wl.n_seq):                           # blocks before the first changed one were not written
+        first = int(old_len[s]) // wl.B
+        assert torch.equal(Kp[s, :first], stale[s, :first])
+    # a bound of one block updates only the block of from_token
+    Kp1 = stale.clone()
+    misa.pool_keys_update(p_new, dv["K"], dv["kscale"], Kp1, old_dev, 1, ws)
+    for s in range(wl.n_seq):
+        first = int(old_len[s]) // wl.B
+        if first * wl.B < int(new_len[s]):
+            assert torch.equal(Kp1[s, first], full[s, first])
+        assert torch.equal(Kp1[s, first + 1:], stale[s, first + 1:])
+
+
 def test_pool_B1_decodes_all_fp8_codes(misa):
     # With B = 1 pooling returns the de-quantised keys themselves, so this
     # checks the hardware fp8 decode against the oracle's table for every code.

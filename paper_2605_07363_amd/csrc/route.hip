@@ -17,6 +17,8 @@
 // route_finalize_kernel: adds the causal tail block (mean of the raw keys of
 // the last, partial block of a query that does not sit at the end of the
 // cache), scales by |w| / M_n and selects the top-h heads by rank counting.
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace misa {
@@ -242,6 +244,114 @@ __global__ __launch_bounds__(256) void route_tile_kernel(Prob p, int splits,
     }
 }
 
+// Few query-head rows (decode: n_q * H <= 64): every wavefront works alone on its own tiles
+// of 32 pooled blocks, which it loads straight into matrix fragments (a lane reads 32
+// contiguous bytes of one pooled key per k-step) and splits into bf16 hi/lo pieces in
+// registers: no LDS, no barrier, one round of loads per tile.  RT = 32-row tiles in use.
+template <int RT>
+__global__ __launch_bounds__(256) void route_wave_kernel(Prob p, int tiles_per_wave, int n_parts,
+                                                         const uint16_t* __restrict__ Q,
+                                                         const float* __restrict__ Kp,
+                                                         float* __restrict__ part) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, hf = lane >> 5;
+  const int seq = blockIdx.y;
+  const int pi = blockIdx.x * 4 + wave;  // partial-sum slot of this wavefront
+  if (pi >= n_parts) return;
+  const int rows_per_seq = p.n_q * p.H;
+  const int len = seq_length(p, seq);
+  // row / H for rows < 64 by one multiplication: exact because row * (H * inv - 65536) < 65536
+  const uint32_t inv = (65536u + (uint32_t)p.H - 1u) / (uint32_t)p.H;
+
+  RFrag a[RT][8];
+  int nb[RT][16];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const int row = rt * 32 + col;
+    const uint16_t* src = Q + ((size_t)seq * rows_per_seq + min(row, rows_per_seq - 1)) * kD + hf * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const uint4 v = *reinterpret_cast<const uint4*>(src + ks * 16);
+      a[rt][ks].u = row < rows_per_seq ? v : make_uint4(0, 0, 0, 0);
+    }
+    int t_prev = -1, nb_prev = 0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int rr = rt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+      int v = 0;
+      if (rr < rows_per_seq) {
+        const int t = (int)(((uint32_t)rr * inv) >> 16);
+        if (t != t_prev) { nb_prev = pooled_blocks(visible(p, seq, t), len, p.B); t_prev = t; }
+        v = nb_prev;
+      }
+      nb[rt][r] = v;
+    }
+  }
+  float sum[RT][16];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum[rt][r] = 0.f;
+
+  const float* kp_seq = Kp + (size_t)seq * p.M * kD;
+  for (int tl = 0; tl < tiles_per_wave; ++tl) {
+    const int b0 = (pi * tiles_per_wave + tl) * kRouteKT;
+    if (b0 >= p.M) break;
+    const float* src = kp_seq + (size_t)min(b0 + col, p.M - 1) * kD + hf * 8;
+    float4 x[8][2];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      x[ks][0] = *reinterpret_cast<const float4*>(src + ks * 16);
+      x[ks][1] = *reinterpret_cast<const float4*>(src + ks * 16 + 4);
+    }
+    f32x16 acc[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[rt][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const float v[8] = {x[ks][0].x, x[ks][0].y, x[ks][0].z, x[ks][0].w,
+                          x[ks][1].x, x[ks][1].y, x[ks][1].z, x[ks][1].w};
+      uint32_t hi[8], lo[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint32_t u = __float_as_uint(v[j]);
+        hi[j] = u & 0xFFFF0000u;                                   // upper 16 bits: exact bf16
+        lo[j] = __float_as_uint(v[j] - __uint_as_float(hi[j])) & 0xFFFF0000u;
+      }
+      RFrag bh, bl;
+      bh.u = make_uint4((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3], (hi[4] >> 16) | hi[5], (hi[6] >> 16) | hi[7]);
+      bl.u = make_uint4((lo[0] >> 16) | lo[1], (lo[2] >> 16) | lo[3], (lo[4] >> 16) | lo[5], (lo[6] >> 16) | lo[7]);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, bh.v, acc[rt], 0, 0, 0);
+        acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, bl.v, acc[rt], 0, 0, 0);
+      }
+    }
+    const int b = b0 + col;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum[rt][r] += (b < nb[rt][r] && b < p.M) ? relu(acc[rt][r]) : 0.f;
+  }
+
+  // sum over the 32 block columns of each half-wave, then one lane per row writes
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float v = sum[rt][r];
+#pragma unroll
+      for (int o = 16; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+      const int rr = rt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+      if (col == 0 && rr < rows_per_seq) {
+        const int t = (int)(((uint32_t)rr * inv) >> 16), j = rr - t * p.H;
+        part[(((size_t)seq * p.n_q + t) * n_parts + pi) * kWave + j] = v;
+      }
+    }
+}
+
 template <int KDT, int QDT>
 __global__ __launch_bounds__(128) void route_finalize_kernel(
     Prob p, int splits, const void* __restrict__ Q, const float* __restrict__ W,
@@ -280,9 +390,16 @@ __global__ __launch_bounds__(128) void route_finalize_kernel(
 
   if (tid < p.H) {
     const size_t qi = ((size_t)seq * p.n_q + t) * p.H + tid;
+    // partial sums are added in slot order; eight loads are in flight at a time
     float s = 0.f;
-    for (int sp = 0; sp < splits; ++sp)
-      s += part[(((size_t)seq * p.n_q + t) * splits + sp) * kWave + tid];
+    const float* ps = part + ((size_t)seq * p.n_q + t) * splits * kWave + tid;
+    for (int sp = 0; sp < splits; sp += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = sp + u < splits ? ps[(size_t)(sp + u) * kWave] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
     if (tail) {
       float qv[kD];
       load_query_head<QDT>(Q, qi, qv);
@@ -391,9 +508,23 @@ int route_splits(const Prob& p) {
   return (int)s;
 }
 
+// The per-wavefront kernel is used when all (query, head) rows of a sequence fit one wavefront.
+static bool route_by_wave(const Prob& p) { return (long long)p.n_q * p.H <= 64; }
+
+// Tiles per wavefront and partial sums per query of the per-wavefront kernel: one tile each
+// up to 64 partial sums, more tiles per wavefront beyond.
+static void route_wave_shape(const Prob& p, int* tiles_per_wave, int* n_parts) {
+  const int tiles = (p.M + kRouteKT - 1) / kRouteKT;
+  *tiles_per_wave = (tiles + 63) / 64;
+  *n_parts = (tiles + *tiles_per_wave - 1) / *tiles_per_wave;
+}
+
 size_t route_ws_bytes(const Prob& p) {
-  // partial sums [n_seq, n_q, splits * 4, 64]: room for every column phase of the tiled kernel
-  return (size_t)p.n_seq * p.n_q * route_splits(p) * 4 * kWave * sizeof(float);
+  // partial sums [n_seq, n_q, parts, 64]; the tiled kernel needs room for every column phase
+  // (splits * 4), the per-wavefront kernel for its (at most 64) parts
+  size_t parts = (size_t)route_splits(p) * 4;
+  if (route_by_wave(p)) parts = std::max<size_t>(parts, 64);
+  return (size_t)p.n_seq * p.n_q * parts * kWave * sizeof(float);
 }
 
 hipError_t launch_route(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,
@@ -402,7 +533,15 @@ hipError_t launch_route(const Prob& p, int k_dtype, int q_dtype, const void* Q, 
   const int splits = route_splits(p);
   float* part = static_cast<float*>(ws);
   int total_splits = splits;
-  if (q_dtype == MISA_BF16) {
+  if (q_dtype == MISA_BF16 && route_by_wave(p)) {
+    int tpw, parts;
+    route_wave_shape(p, &tpw, &parts);
+    total_splits = parts;
+    const dim3 g1((parts + 3) / 4, p.n_seq);
+    const uint16_t* q = static_cast<const uint16_t*>(Q);
+    if (p.n_q * p.H <= 32) route_wave_kernel<1><<<g1, 256, 0, st>>>(p, tpw, parts, q, Kp, part);
+    else route_wave_kernel<2><<<g1, 256, 0, st>>>(p, tpw, parts, q, Kp, part);
+  } else if (q_dtype == MISA_BF16) {
     const int rg = route_row_groups(p);
     total_splits = splits * (4 / rg);
     const int rows = p.n_q * p.H;

@@ -44,7 +44,7 @@ __all__ = [
     "e4m3fn_decode_table", "bf16_bits_to_f64", "dequantise",
     "pool_keys", "route_affinity", "route_heads", "route_heads_proxy", "score_tokens", "dsa_scores",
     "topk", "rerank", "misa", "misa_dagger", "dsa_dense", "iou", "recall",
-    "head_token_products",
+    "head_token_products", "block_scores", "select_blocks", "block_tokens", "hisa", "block_sparse",
 ]
 
 
@@ -237,6 +237,65 @@ def rerank(q, w, K, cand, k: int, n: int | None = None):
     sub = dense[cand]                          # ... restricted to Omega_t
     keep = _top_by_value_then_index(sub, k)    # ascending position == ascending token
     return cand[keep], sub[keep]
+
+
+# --------------------------------------------------------------------------
+# Comparison indexers built from the same parts: HISA (preliminaries, "Indexer
+# in HISA", Eq. block_score and Eq. final_topk) and the MoBA-style Block-Sparse
+# selector (Experimental results, "Baselines")
+# --------------------------------------------------------------------------
+def block_scores(q, w, K, B: int, n: int | None = None) -> np.ndarray:
+    """J[b] = sum over all heads of w_j * ReLU(q_j . k~_b) for the M = ceil(n/B) pooled
+    keys of the visible prefix (Eq. block_score, left part)."""
+    Kp = pool_keys(K, B, n)
+    if Kp.shape[0] == 0:
+        return np.zeros(0, dtype=np.float64)
+    return route_affinity(q, w, Kp).sum(axis=0)
+
+
+def select_blocks(J: np.ndarray, m: int) -> np.ndarray:
+    """C = the first and the last block plus the best-scoring other blocks, m blocks in
+    all (every block if there are at most m); ties to the lower index; ascending
+    (Eq. block_score, right part, with the always-included first and last block)."""
+    J = np.asarray(J, dtype=np.float64)
+    M = J.shape[0]
+    if m < 2:
+        raise ValueError("m must be >= 2 (the first and the last block are always kept)")
+    if M <= m:
+        return np.arange(M, dtype=np.int64)
+    forced = [0, M - 1]
+    rest = [b for b in range(M) if b not in forced]
+    best = _top_by_value_then_index(J[rest], m - len(forced))
+    return np.array(sorted(forced + [rest[i] for i in best.tolist()]), dtype=np.int64)
+
+
+def block_tokens(blocks: np.ndarray, B: int, n: int) -> np.ndarray:
+    """Omega = the visible tokens of the given blocks, ascending."""
+    out = [s for b in np.asarray(blocks).tolist() for s in range(b * B, min((b + 1) * B, n))]
+    return np.array(out, dtype=np.int64)
+
+
+def hisa(q, w, K, B: int, m: int, k: int, n: int | None = None) -> dict:
+    """HISA indexer: top-m blocks by the all-head block score, then the dense indexer score
+    inside those blocks and its top-k (Eq. block_score, Eq. final_topk)."""
+    n = np.asarray(K).shape[0] if n is None else int(n)
+    J = block_scores(q, w, K, B, n)
+    if n == 0:
+        return {"J": J, "blocks": np.zeros(0, np.int64), "tokens": np.zeros(0, np.int64),
+                "values": np.zeros(0)}
+    C = select_blocks(J, m)
+    tokens, vals = rerank(q, w, K, block_tokens(C, B, n), k, n)
+    return {"J": J, "blocks": C, "tokens": tokens, "values": vals}
+
+
+def block_sparse(q, w, K, B: int, m: int, n: int | None = None) -> dict:
+    """Block-Sparse selector: the tokens of the m selected blocks are the selection."""
+    n = np.asarray(K).shape[0] if n is None else int(n)
+    J = block_scores(q, w, K, B, n)
+    if n == 0:
+        return {"J": J, "blocks": np.zeros(0, np.int64), "tokens": np.zeros(0, np.int64)}
+    C = select_blocks(J, m)
+    return {"J": J, "blocks": C, "tokens": block_tokens(C, B, n)}
 
 
 # --------------------------------------------------------------------------

@@ -395,3 +395,71 @@ def test_proxy_router_scores_closed_forms():
         O.route_heads_proxy(q, w, 0, "gate")
     with pytest.raises(ValueError):
         O.route_heads_proxy(q, w, h, "pooled")
+
+
+# ---------------------------------------------------------------- HISA / Block-Sparse comparison indexers
+def test_block_scores_link_to_router_and_brute_force():
+    # Eq. block_score and Eq. misa_route_score are the two marginals of the same affinity
+    # matrix: with non-negative gates, sum_b J_b == M * sum_j E_j.
+    rng = np.random.default_rng(51)
+    H, d, L, B = 6, 8, 37, 5
+    q = rng.standard_normal((H, d)); K = rng.standard_normal((L, d)); w = np.abs(rng.standard_normal(H))
+    for n in (37, 35, 12, 5, 1):
+        J = O.block_scores(q, w, K, B, n)
+        _, E = O.route_heads(q, w, K, B, 2, n)
+        M = -(-n // B)
+        assert J.shape == (M,)
+        np.testing.assert_allclose(J.sum(), M * E.sum(), rtol=1e-12)
+        # brute force in exact rational arithmetic on a rounded copy
+        qf = [[Fraction(float(np.round(x, 3))) for x in row] for row in q]
+        Kf = [[Fraction(float(np.round(x, 3))) for x in row] for row in K]
+        wf = [Fraction(float(np.round(x, 3))) for x in w]
+        Jr = O.block_scores(np.round(q, 3), np.round(w, 3), np.round(K, 3), B, n)
+        for b in range(M):
+            rows = range(b * B, min((b + 1) * B, n))
+            mean = [sum(Kf[s][c] for s in rows) / len(rows) for c in range(d)]
+            tot = Fraction(0)
+            for j in range(H):
+                dot = sum(qf[j][c] * mean[c] for c in range(d))
+                tot += wf[j] * max(dot, Fraction(0))
+            assert abs(float(tot) - Jr[b]) <= 1e-12 * max(1.0, abs(float(tot)))
+    # signed gates: a head with a negative gate lowers the block score
+    w2 = w.copy(); w2[0] = -w2[0]
+    assert np.all(O.block_scores(q, w2, K, B) <= O.block_scores(q, w, K, B) + 1e-15)
+
+
+def test_select_blocks_keeps_first_and_last():
+    J = np.array([-5.0, 3.0, 9.0, 1.0, 9.0, 2.0, -7.0])
+    np.testing.assert_array_equal(O.select_blocks(J, 2), [0, 6])
+    np.testing.assert_array_equal(O.select_blocks(J, 3), [0, 2, 6])          # tie 9 == 9 -> lower index
+    np.testing.assert_array_equal(O.select_blocks(J, 4), [0, 2, 4, 6])
+    np.testing.assert_array_equal(O.select_blocks(J, 5), [0, 1, 2, 4, 6])
+    np.testing.assert_array_equal(O.select_blocks(J, 7), np.arange(7))
+    np.testing.assert_array_equal(O.select_blocks(J, 50), np.arange(7))
+    np.testing.assert_array_equal(O.select_blocks(np.array([1.0]), 2), [0])
+    with pytest.raises(ValueError):
+        O.select_blocks(J, 1)
+    np.testing.assert_array_equal(O.block_tokens(np.array([0, 2]), 4, 10), [0, 1, 2, 3, 8, 9])
+
+
+def test_hisa_reductions_and_invariants():
+    rng = np.random.default_rng(52)
+    H, d, L, B, k = 5, 8, 64, 8, 10
+    q = rng.standard_normal((H, d)); K = rng.standard_normal((L, d)); w = rng.standard_normal(H)
+    for n in (64, 61, 20):
+        M = -(-n // B)
+        dense = O.dsa_scores(q, w, K, n)
+        full = O.hisa(q, w, K, B, M, k, n)                         # every block kept: the dense indexer
+        np.testing.assert_array_equal(full["tokens"], O.topk(dense, k))
+        r = O.hisa(q, w, K, B, 3, k, n)
+        assert r["blocks"][0] == 0 and r["blocks"][-1] == M - 1 and len(r["blocks"]) == min(3, M)
+        omega = O.block_tokens(r["blocks"], B, n)
+        assert set(r["tokens"].tolist()) <= set(omega.tolist()) and len(r["tokens"]) == min(k, len(omega))
+        # the selection is the dense top-k restricted to Omega
+        sub = O.topk(dense[omega], k)
+        np.testing.assert_array_equal(r["tokens"], omega[sub])
+        np.testing.assert_allclose(r["values"], dense[r["tokens"]], rtol=0, atol=0)
+        bs = O.block_sparse(q, w, K, B, 3, n)
+        np.testing.assert_array_equal(bs["blocks"], r["blocks"])
+        np.testing.assert_array_equal(bs["tokens"], omega)
+    assert O.hisa(q, w, K, B, 3, k, 0)["tokens"].shape == (0,)

@@ -75,7 +75,8 @@ typedef enum misa_op {
   MISA_OP_SCORE = 2,
   MISA_OP_TOPK = 3,
   MISA_OP_RERANK = 4,
-  MISA_OP_SELECT = 5
+  MISA_OP_SELECT = 5,
+  MISA_OP_HISA = 6 /* misa_hisa_select and misa_block_sparse_select; k argument = m */
 } misa_op;
 
 /* Router scores of the routing-score ablation (appendix "Ablation: routing score"). */
@@ -245,6 +246,40 @@ int64_t misa_select_row_flags_offset(const misa_problem* p, int32_t routed, int3
 misa_status misa_rerank(const misa_problem* p, const void* Q, const float* W, const void* K,
                         const float* kscale, const int32_t* cand, int32_t k_cand, int32_t k,
                         int32_t* idx, float* val, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Comparison indexers on the same stages (not part of MISA itself).
+ *
+ * HISA (preliminaries, "Indexer in HISA": Eq. block_score, Eq. final_topk): the
+ * pooled keys of the query's prefix are scored with ALL H heads,
+ *   J[b] = sum_j W[j] * ReLU(Q[j] . k~_b);
+ * the first and the last block of the prefix are always kept and the
+ * best-scoring other blocks are added up to m blocks in all (every block if
+ * the prefix has at most m; ties to the lower index); the tokens of those
+ * blocks are then scored with all heads (Eq. dsa_score) and the best k kept,
+ * as misa_rerank does for its candidates.  Kp is what misa_pool_keys wrote.
+ *   m       blocks kept per query, >= 2, m * B <= 16384
+ *   k       1 <= k <= m * B
+ *   blocks  out  [n_seq, n_q, m] int32 ascending, tail = -1, or NULL
+ *   idx     out  [n_seq, n_q, k] int32 ascending, tail = -1
+ *   val     out  [n_seq, n_q, k] float or NULL (dense scores), tail = -inf
+ */
+misa_status misa_hisa_select(const misa_problem* p, const void* Q, const float* W, const float* Kp,
+                             const void* K, const float* kscale, int32_t m, int32_t k,
+                             int32_t* blocks, int32_t* idx, float* val, void* ws, size_t ws_bytes,
+                             void* stream);
+
+/*
+ * Block-Sparse (Experimental results, "Baselines"; MoBA-style): the same block
+ * choice as the first stage of misa_hisa_select; the visible tokens of the
+ * chosen blocks are the selection (m = k / B gives a budget of k tokens).
+ *   idx  out  [n_seq, n_q, m * B] int32: token o of the i-th chosen block at
+ *             slot i * B + o, -1 where there is no such block or the token is
+ *             not visible (ascending apart from the -1 entries)
+ */
+misa_status misa_block_sparse_select(const misa_problem* p, const void* Q, const float* W,
+                                     const float* Kp, int32_t m, int32_t* blocks, int32_t* idx,
+                                     void* ws, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -79,6 +79,7 @@ misa_status hip_result(hipError_t e, const char* what) {
 size_t ws_bytes_for(const misa::Prob& pr, int op, int k, int k_dtype = 0, int q_dtype = 0) {
   switch (op) {
     case MISA_OP_SELECT: return misa::select_ws_bytes(pr, k_dtype, q_dtype, k);
+    case MISA_OP_HISA: return misa::hisa_ws_bytes(pr, k);
     case MISA_OP_POOL: return misa::pool_ws_bytes(pr);
     case MISA_OP_ROUTE: return misa::route_ws_bytes(pr);
     case MISA_OP_TOPK: return misa::topk_ws_bytes(pr, k);
@@ -99,7 +100,7 @@ const char* misa_last_error(void) { return g_err; }
 size_t misa_workspace_bytes(const misa_problem* p, int32_t op, int32_t k) {
   misa::Prob pr;
   if (check_problem(p, &pr) != MISA_OK) return 0;
-  if (op < MISA_OP_POOL || op > MISA_OP_SELECT) return 0;
+  if (op < MISA_OP_POOL || op > MISA_OP_HISA) return 0;
   return ws_bytes_for(pr, op, k, p->k_dtype, p->q_dtype);
 }
 
@@ -208,6 +209,48 @@ int64_t misa_select_row_flags_offset(const misa_problem* p, int32_t routed, int3
   misa::Prob pr;
   if (check_problem(p, &pr) != MISA_OK) return -1;
   return misa::select_row_flags_offset(pr, p->k_dtype, p->q_dtype, routed != 0, k);
+}
+
+namespace {
+misa_status check_block_budget(const misa::Prob& pr, int32_t m) {
+  if (m < 2) return fail(MISA_ERR_INVALID_ARG, "m must be >= 2: the first and the last block are always kept (got %d)", m);
+  if ((long long)m * pr.B > misa::kMaxTopK)
+    return fail(MISA_ERR_UNSUPPORTED, "m * B must be <= 16384 (m=%d, B=%d)", m, pr.B);
+  return MISA_OK;
+}
+}  // namespace
+
+misa_status misa_hisa_select(const misa_problem* p, const void* Q, const float* W, const float* Kp,
+                             const void* K, const float* kscale, int32_t m, int32_t k, int32_t* blocks,
+                             int32_t* idx, float* val, void* ws, size_t ws_bytes, void* stream) {
+  misa::Prob pr;
+  misa_status st = check_problem(p, &pr);
+  if (st != MISA_OK) return st;
+  if ((st = check_queries(Q, W)) != MISA_OK) return st;
+  if ((st = check_keys(p, K, kscale)) != MISA_OK) return st;
+  if (!Kp || !idx) return fail(MISA_ERR_INVALID_ARG, "Kp or idx is NULL");
+  if ((st = check_block_budget(pr, m)) != MISA_OK) return st;
+  if (k < 1 || (long long)k > (long long)m * pr.B)
+    return fail(MISA_ERR_INVALID_ARG, "need 1 <= k <= m * B (k=%d, m=%d, B=%d)", k, m, pr.B);
+  if ((st = check_ws(ws_bytes_for(pr, MISA_OP_HISA, m), ws, ws_bytes)) != MISA_OK) return st;
+  return hip_result(misa::launch_hisa(pr, p->k_dtype, p->q_dtype, Q, W, Kp, K, kscale, m, k, blocks, idx,
+                                      val, ws, (hipStream_t)stream),
+                    "misa_hisa_select launch");
+}
+
+misa_status misa_block_sparse_select(const misa_problem* p, const void* Q, const float* W,
+                                     const float* Kp, int32_t m, int32_t* blocks, int32_t* idx, void* ws,
+                                     size_t ws_bytes, void* stream) {
+  misa::Prob pr;
+  misa_status st = check_problem(p, &pr);
+  if (st != MISA_OK) return st;
+  if ((st = check_queries(Q, W)) != MISA_OK) return st;
+  if (!Kp || !idx) return fail(MISA_ERR_INVALID_ARG, "Kp or idx is NULL");
+  if ((st = check_block_budget(pr, m)) != MISA_OK) return st;
+  if ((st = check_ws(ws_bytes_for(pr, MISA_OP_HISA, m), ws, ws_bytes)) != MISA_OK) return st;
+  return hip_result(misa::launch_hisa(pr, p->k_dtype, p->q_dtype, Q, W, Kp, nullptr, nullptr, m, 0, blocks,
+                                      idx, nullptr, ws, (hipStream_t)stream),
+                    "misa_block_sparse_select launch");
 }
 
 misa_status misa_rerank(const misa_problem* p, const void* Q, const float* W, const void* K,

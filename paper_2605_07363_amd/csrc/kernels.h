@@ -59,7 +59,16 @@ constexpr int kMaxTopK = 16384;
 constexpr int kMaxRowLen = 524288;
 size_t topk_ws_bytes(const Prob& p, int k);
 // only != nullptr: rows r with only[r] == 0 are left untouched (ws is not needed then).
+// all_slots (with map == nullptr): row r scans all row_len slots, never selects -inf slots
+// and reports positions.
 hipError_t launch_topk(const Prob& p, const float* S, int row_len, int k, const int* map, int* idx,
-                       float* val, void* ws, hipStream_t st, const int* only = nullptr);
+                       float* val, void* ws, hipStream_t st, const int* only = nullptr,
+                       bool all_slots = false);
+
+// HISA and Block-Sparse comparison indexers (hisa.hip); k == 0 selects Block-Sparse.
+size_t hisa_ws_bytes(const Prob& p, int m);
+hipError_t launch_hisa(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,
+                       const float* Kp, const void* K, const float* kscale, int m, int k, int* blocks,
+                       int* idx, float* val, void* ws, hipStream_t st);
 
 }  // namespace misa

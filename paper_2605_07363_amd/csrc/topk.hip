@@ -127,7 +127,7 @@ template <bool PRE>
 __device__ __forceinline__ void topk_row(const Prob& p, const float* __restrict__ S, int row_len,
                                          int k, const int* __restrict__ map, int* __restrict__ idx,
                                          float* __restrict__ val, const int* __restrict__ pre, int t,
-                                         int seq, uint32_t* dyn) {
+                                         int seq, uint32_t* dyn, bool all_slots = false) {
   // dyn: sel bitmap, then eq bitmap OR boundary list (keys, idx)
   __shared__ int hist[kBins];
   __shared__ int scan_scratch[32];
@@ -137,7 +137,7 @@ __device__ __forceinline__ void topk_row(const Prob& p, const float* __restrict_
   const int tid = threadIdx.x;
   const size_t row = (size_t)seq * p.n_q + t;
   const float* s = S + row * row_len;
-  const int n = map ? row_len : visible(p, seq, t);
+  const int n = (map || all_slots) ? row_len : visible(p, seq, t);
   const int nwords_max = (row_len + 31) / 32;
   uint32_t* sel = dyn;
   uint32_t* eq = dyn + nwords_max;       // fallback path
@@ -163,7 +163,7 @@ __device__ __forceinline__ void topk_row(const Prob& p, const float* __restrict_
   }
 
   int selectable = n;
-  if (map) {  // never select -inf slots (skipped candidates): they live in bins <= 3
+  if (map || all_slots) {  // never select -inf slots (skipped candidates): they live in bins <= 3
     selectable = n - (hist[0] + hist[1] + hist[2] + hist[3]);
   }
   const int k_eff = min(k, selectable);
@@ -356,9 +356,10 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(Prob p, const float*
                                                             const int* __restrict__ map,
                                                             int* __restrict__ idx,
                                                             float* __restrict__ val,
-                                                            const int* __restrict__ pre) {
+                                                            const int* __restrict__ pre,
+                                                            bool all_slots) {
   extern __shared__ uint32_t dyn[];
-  topk_row<PRE>(p, S, row_len, k, map, idx, val, pre, blockIdx.x, blockIdx.y, dyn);
+  topk_row<PRE>(p, S, row_len, k, map, idx, val, pre, blockIdx.x, blockIdx.y, dyn, all_slots);
 }
 
 // Only the rows r with only[r] != 0 (rows another path could not finish).  Normally
@@ -409,7 +410,7 @@ static hipError_t set_lds_limit(size_t lds) {
 }
 
 hipError_t launch_topk(const Prob& p, const float* S, int row_len, int k, const int* map, int* idx,
-                       float* val, void* ws, hipStream_t st, const int* only) {
+                       float* val, void* ws, hipStream_t st, const int* only, bool all_slots) {
   const size_t nwords = (size_t)(row_len + 31) / 32;
   const size_t second = nwords * 4 > (size_t)kCap * 8 ? nwords * 4 : (size_t)kCap * 8;
   const size_t lds = nwords * 4 + second;
@@ -421,7 +422,7 @@ hipError_t launch_topk(const Prob& p, const float* S, int row_len, int k, const 
     topk_only_kernel<<<rows < 256 ? rows : 256, kTopkThreads, lds, st>>>(p, S, k, idx, val, only);
     return hipGetLastError();
   }
-  if (!map && use_split(p)) {
+  if (!map && !all_slots && use_split(p)) {
     int* pre = static_cast<int*>(ws);
     const int stride = (kPreHeader + k + 2 * kCap + 63) & ~63;
     const int rows = p.n_seq * p.n_q;
@@ -431,12 +432,12 @@ hipError_t launch_topk(const Prob& p, const float* S, int row_len, int k, const 
     topk_partition_kernel<<<g2, kTopkThreads, 0, st>>>(p, S, k, pre);
     hipError_t e = set_lds_limit<1>(lds);
     if (e != hipSuccess) return e;
-    topk_kernel<true><<<grid, kTopkThreads, lds, st>>>(p, S, row_len, k, map, idx, val, pre);
+    topk_kernel<true><<<grid, kTopkThreads, lds, st>>>(p, S, row_len, k, map, idx, val, pre, false);
     return hipGetLastError();
   }
   hipError_t e = set_lds_limit<0>(lds);
   if (e != hipSuccess) return e;
-  topk_kernel<false><<<grid, kTopkThreads, lds, st>>>(p, S, row_len, k, map, idx, val, nullptr);
+  topk_kernel<false><<<grid, kTopkThreads, lds, st>>>(p, S, row_len, k, map, idx, val, nullptr, all_slots);
   return hipGetLastError();
 }
 

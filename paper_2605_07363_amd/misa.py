@@ -23,7 +23,7 @@ lib = ctypes.CDLL(LIB_PATH)
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
 DTYPE_CODES = {"f32": F32, "bf16": BF16, "e4m3": FP8_E4M3}
-OP_POOL, OP_ROUTE, OP_SCORE, OP_TOPK, OP_RERANK, OP_SELECT = range(6)
+OP_POOL, OP_ROUTE, OP_SCORE, OP_TOPK, OP_RERANK, OP_SELECT, OP_HISA = range(7)
 STATUS_NAMES = {0: "MISA_OK", 1: "MISA_ERR_INVALID_ARG", 2: "MISA_ERR_UNSUPPORTED",
                 3: "MISA_ERR_WORKSPACE", 4: "MISA_ERR_HIP"}
 
@@ -57,6 +57,11 @@ lib.misa_select_tokens.restype = ctypes.c_int
 lib.misa_select_tokens.argtypes = [_P, _V, _V, _V, _V, _V, ctypes.c_int32, _V, _V, _V, ctypes.c_size_t, _V]
 lib.misa_select_row_flags_offset.restype = ctypes.c_int64
 lib.misa_select_row_flags_offset.argtypes = [_P, ctypes.c_int32, ctypes.c_int32]
+lib.misa_hisa_select.restype = ctypes.c_int
+lib.misa_hisa_select.argtypes = [_P, _V, _V, _V, _V, _V, ctypes.c_int32, ctypes.c_int32, _V, _V, _V, _V,
+                                 ctypes.c_size_t, _V]
+lib.misa_block_sparse_select.restype = ctypes.c_int
+lib.misa_block_sparse_select.argtypes = [_P, _V, _V, _V, ctypes.c_int32, _V, _V, _V, ctypes.c_size_t, _V]
 lib.misa_rerank.restype = ctypes.c_int
 lib.misa_rerank.argtypes = [_P, _V, _V, _V, _V, _V, ctypes.c_int32, ctypes.c_int32, _V, _V, _V,
                             ctypes.c_size_t, _V]
@@ -189,6 +194,18 @@ def rerank(p: Problem, Q, W, K, kscale, cand, k_cand: int, k: int, idx, val=None
     w, wb = _ws(ws)
     _check(lib.misa_rerank(ctypes.byref(p.c()), _ptr(Q), _ptr(W), _ptr(K), _ptr(kscale), _ptr(cand),
                            k_cand, k, _ptr(idx), _ptr(val), w, wb, _stream()))
+
+
+def hisa_select(p: Problem, Q, W, Kp, K, kscale, m: int, k: int, idx, val=None, blocks=None, ws=None) -> None:
+    w, wb = _ws(ws)
+    _check(lib.misa_hisa_select(ctypes.byref(p.c()), _ptr(Q), _ptr(W), _ptr(Kp), _ptr(K), _ptr(kscale), m, k,
+                                _ptr(blocks), _ptr(idx), _ptr(val), w, wb, _stream()))
+
+
+def block_sparse_select(p: Problem, Q, W, Kp, m: int, idx, blocks=None, ws=None) -> None:
+    w, wb = _ws(ws)
+    _check(lib.misa_block_sparse_select(ctypes.byref(p.c()), _ptr(Q), _ptr(W), _ptr(Kp), m, _ptr(blocks),
+                                        _ptr(idx), w, wb, _stream()))
 
 
 # ---------------------------------------------------------------------------

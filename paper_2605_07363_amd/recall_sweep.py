@@ -9,7 +9,7 @@ Eq. misa_topk) and once with the dense re-rank of k' = 4k candidates (Eq.
 misa_final_topk), and reports which fraction of the dense all-head top-k set
 (Eq. dsa_topk) each selection recovers; the same for the two content-free
 router scores of the appendix "Ablation: routing score" (gate alone, query
-norm).  The inputs are the seeded synthetic
+norm) and for the HISA and Block-Sparse comparison indexers at B = 128.  The inputs are the seeded synthetic
 caches of workloads.py, so the figures describe those inputs, not a trained
 model.
 
@@ -87,9 +87,23 @@ def main() -> int:
         proxy.append(row)
         print(f"router ablation h={h:3d}  gate {row['gate_recall']:.4f}  query norm {row['query_norm_recall']:.4f}",
               file=sys.stderr, flush=True)
+    # comparison indexers with the paper's baseline block size B = 128 and the same token budget
+    bp = problem(base.h, 128)
+    Kp = torch.empty((base.n_seq, bp.M, base.d), dtype=torch.float32, device="cuda")
+    misa.pool_keys(bp, K, ks, Kp, misa.alloc_workspace(bp, misa.OP_POOL))
+    baselines = {}
+    m_hisa = 4 * base.k // 128                      # candidate tokens = 4k, as MISA-dagger's k'
+    idx = torch.empty((base.n_seq, base.n_q, base.k), dtype=torch.int32, device="cuda")
+    misa.hisa_select(bp, Q, W, Kp, K, ks, m_hisa, base.k, idx, None, None, misa.alloc_workspace(bp, misa.OP_HISA, m_hisa))
+    baselines["hisa_B128_m%d_recall" % m_hisa] = round(overlap(idx.view(rows, -1), ref), 4)
+    m_bs = base.k // 128                            # m = k / B blocks
+    bidx = torch.empty((base.n_seq, base.n_q, m_bs * 128), dtype=torch.int32, device="cuda")
+    misa.block_sparse_select(bp, Q, W, Kp, m_bs, bidx, None, misa.alloc_workspace(bp, misa.OP_HISA, m_bs))
+    baselines["block_sparse_B128_m%d_recall" % m_bs] = round(overlap(bidx.view(rows, -1), ref), 4)
+    print("comparison indexers:", baselines, file=sys.stderr, flush=True)
     torch.cuda.synchronize()
     print(json.dumps({"workload": base.name, "n_seq": base.n_seq, "L": base.L, "H": base.H, "k": base.k,
-                      "rows": out, "router_ablation": proxy}))
+                      "rows": out, "router_ablation": proxy, "baselines": baselines}))
     return 0
 
 

@@ -1,0 +1,140 @@
+"""GPU parity tests of the comparison indexers misa_hisa_select and
+misa_block_sparse_select (Eq. block_score, Eq. final_topk; "Baselines") against the
+fp64 oracle: chosen blocks by the margin rule on the oracle's block scores (first and last
+block always present), final tokens by the margin rule on the dense scores inside the
+blocks the GPU chose, values within the score tolerance."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import misa_oracle as O
+from paper_2605_07363_amd import workloads as WL
+from helpers import oracle_view, assert_scores_close, check_index_set
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def misa():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2605_07363_amd import misa as m
+    return m
+
+
+def small(base, **kw):
+    return WL.scaled(WL.WORKLOADS[base], **kw)
+
+
+CASES = {
+    # name: (workload, m)
+    "bf16_decode": (small("c1", n_seq=3, L=5000, B=128, k=300), 6),
+    "fp8_decode": (small("c3", n_seq=2, L=4133, B=128, k=512, needles=16), 8),
+    "f32_decode": (small("c0", L=1500, B=64, k=100), 4),
+    "bf16_prefill": (small("c2", L=3000, n_q=37, B=64, k=200), 9),
+    "fp8_prefill": (small("c4", L=2500, n_q=20, B=32, k=128, k_cand=0, needles=16), 12),
+    "all_blocks": (small("c1", n_seq=2, L=1000, B=100, k=64), 16),       # m >= M: the dense indexer
+    "two_blocks": (small("c2", L=2000, n_q=9, B=50, k=60), 2),           # only the forced blocks
+}
+
+
+def forced_scores(J):
+    J = J.copy()
+    if J.shape[0]:
+        J[0] = np.inf
+        J[-1] = np.inf
+    return J
+
+
+def run(misa, name, seq_len=None, q_pos=None):
+    wl, m = CASES[name]
+    inp = WL.make_inputs(wl, seed=300 + sum(map(ord, name)), seq_len=seq_len)
+    if q_pos is not None:
+        inp["q_pos"] = np.asarray(q_pos, dtype=np.int32)
+    dv = misa.to_device(inp)
+    p = dv["problem"]
+    rows = (wl.n_seq, wl.n_q)
+    Kp = torch.empty((wl.n_seq, p.M, wl.d), dtype=torch.float32, device="cuda")
+    misa.pool_keys(p, dv["K"], dv["kscale"], Kp, misa.alloc_workspace(p, misa.OP_POOL))
+    blocks = torch.full(rows + (m,), -9, dtype=torch.int32, device="cuda")
+    idx = torch.full(rows + (wl.k,), -9, dtype=torch.int32, device="cuda")
+    val = torch.full(rows + (wl.k,), 9.0, dtype=torch.float32, device="cuda")
+    ws = misa.alloc_workspace(p, misa.OP_HISA, m)
+    misa.hisa_select(p, dv["Q"], dv["W"], Kp, dv["K"], dv["kscale"], m, wl.k, idx, val, blocks, ws)
+    bs_blocks = torch.full(rows + (m,), -9, dtype=torch.int32, device="cuda")
+    bs_idx = torch.full(rows + (m * wl.B,), -9, dtype=torch.int32, device="cuda")
+    misa.block_sparse_select(p, dv["Q"], dv["W"], Kp, m, bs_idx, bs_blocks, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(blocks, bs_blocks)
+    return inp, wl, m, blocks.cpu().numpy(), idx.cpu().numpy(), val.cpu().numpy(), bs_idx.cpu().numpy()
+
+
+def check(inp, wl, m, blocks, idx, val, bs_idx):
+    exact = 0
+    for s in range(wl.n_seq):
+        for t in range(wl.n_q):
+            K, q, w, n = oracle_view(inp, s, t)
+            what = f"{wl.name} row {s},{t} (n={n})"
+            J = O.block_scores(q, w, K, wl.B, n)
+            M = J.shape[0]
+            got_blocks = blocks[s, t]
+            check_index_set(got_blocks, forced_scores(J), m, "blocks " + what)
+            chosen = got_blocks[got_blocks >= 0]
+            if M:
+                assert chosen[0] == 0 and chosen[-1] == M - 1, what
+            exact += np.array_equal(chosen, O.select_blocks(J, m)) if M else 1
+            omega = O.block_tokens(chosen, wl.B, n)
+            # Block-Sparse: the tokens of the chosen blocks at their slots
+            expect = np.full(m * wl.B, -1, dtype=np.int64)
+            for i, b in enumerate(chosen.tolist()):
+                toks = np.arange(b * wl.B, min((b + 1) * wl.B, n))
+                expect[i * wl.B:i * wl.B + toks.shape[0]] = toks
+            np.testing.assert_array_equal(bs_idx[s, t], expect, err_msg=what)
+            # HISA fine stage on the GPU's blocks
+            dense = O.dsa_scores(q, w, K, n)
+            final = idx[s, t][idx[s, t] >= 0]
+            assert set(final.tolist()) <= set(omega.tolist()), what
+            pos = np.searchsorted(omega, final)
+            padded = np.concatenate([pos, np.full(wl.k - pos.shape[0], -1, dtype=pos.dtype)])
+            check_index_set(padded, dense[omega], wl.k, "tokens " + what)
+            assert_scores_close(val[s, t, :final.shape[0]], dense[final], "values " + what)
+            assert np.all(np.isneginf(val[s, t, final.shape[0]:]))
+    return exact
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_hisa_and_block_sparse_match_oracle(misa, name):
+    inp, wl, m, blocks, idx, val, bs_idx = run(misa, name)
+    exact = check(inp, wl, m, blocks, idx, val, bs_idx)
+    assert exact >= 0.9 * wl.n_seq * wl.n_q
+
+
+def test_hisa_with_all_blocks_is_the_dense_indexer(misa):
+    inp, wl, m, blocks, idx, val, _ = run(misa, "all_blocks")
+    for s in range(wl.n_seq):
+        K, q, w, n = oracle_view(inp, s, 0)
+        dense = O.dsa_scores(q, w, K, n)
+        check_index_set(idx[s, 0], dense, wl.k, f"dense seq {s}")
+
+
+def test_hisa_ragged_and_early_queries(misa):
+    wl, m = CASES["bf16_prefill"]
+    q_pos = sorted([0, 1, 63, 64, 65, 127, 128, 500, 1279, 1280, 1281] + list(range(2974, 3000)))
+    assert len(q_pos) == wl.n_q
+    inp, wl, m, blocks, idx, val, bs_idx = run(misa, "bf16_prefill", seq_len=np.array([2100], dtype=np.int32),
+                                               q_pos=q_pos)
+    check(inp, wl, m, blocks, idx, val, bs_idx)
+
+
+def test_hisa_argument_checks(misa):
+    wl, _ = CASES["bf16_decode"]
+    dv = misa.to_device(WL.make_inputs(wl, seed=1))
+    p = dv["problem"]
+    Kp = torch.zeros((wl.n_seq, p.M, wl.d), dtype=torch.float32, device="cuda")
+    idx = torch.zeros((wl.n_seq, 1, 64), dtype=torch.int32, device="cuda")
+    ws = misa.alloc_workspace(p, misa.OP_HISA, 4)
+    for m, k in ((1, 64), (129, 64), (4, 0), (4, 4 * 128 + 1)):
+        with pytest.raises(misa.MisaError):
+            misa.hisa_select(p, dv["Q"], dv["W"], Kp, dv["K"], dv["kscale"], m, k, idx, None, None, ws)
+    with pytest.raises(misa.MisaError):
+        misa.hisa_select(p, dv["Q"], dv["W"], Kp, dv["K"], dv["kscale"], 4, 64, idx, None, None, None)

@@ -369,20 +369,22 @@ __global__ __launch_bounds__(128) void route_finalize_kernel(
 
   if (tail) {  // mean of keys nfull*B .. n-1, component tid
     const char* base = static_cast<const char*>(K) + (size_t)seq * p.L * KV::ROW_BYTES;
-    float s = 0.f;
-    for (int row = nfull * p.B; row < n; ++row) {
+    auto key_component = [&](int row) {
       const char* src = base + (size_t)row * KV::ROW_BYTES;
-      float v;
-      if (KDT == MISA_F32) {
-        v = reinterpret_cast<const float*>(src)[tid];
-      } else if (KDT == MISA_BF16) {
-        v = bf16_bits_to_float(reinterpret_cast<const uint16_t*>(src)[tid]);
-      } else {
-        const uint32_t w = reinterpret_cast<const uint32_t*>(src)[tid >> 2];
-        const f32x2 pr = __builtin_amdgcn_cvt_pk_f32_fp8(w >> ((tid & 2) * 8), false);
-        v = pr[tid & 1] * kscale[(size_t)seq * p.L + row];
-      }
-      s += v;
+      if (KDT == MISA_F32) return reinterpret_cast<const float*>(src)[tid];
+      if (KDT == MISA_BF16) return bf16_bits_to_float(reinterpret_cast<const uint16_t*>(src)[tid]);
+      const uint32_t w = reinterpret_cast<const uint32_t*>(src)[tid >> 2];
+      const f32x2 pr = __builtin_amdgcn_cvt_pk_f32_fp8(w >> ((tid & 2) * 8), false);
+      return pr[tid & 1] * kscale[(size_t)seq * p.L + row];
+    };
+    // rows are added in order; eight loads are in flight at a time
+    float s = 0.f;
+    for (int row = nfull * p.B; row < n; row += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = key_component(min(row + u, n - 1));
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += row + u < n ? v[u] : 0.f;
     }
     tailk[tid] = s / (float)r;
   }

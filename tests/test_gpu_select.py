@@ -39,6 +39,8 @@ CASES = {
     "fp8_dense64": (small("c4", L=4200, n_q=19, k=128, k_cand=0, needles=8), False),
     "bf16_bigk": (small("c2", L=20000, n_q=33, k=8192), True),
     "bf16_k1": (small("c2", L=4100, n_q=9, k=1), True),
+    "fp8_h32": (small("c4", L=4800, n_q=11, h=32, k=150, k_cand=0, needles=8), True),
+    "bf16_h3": (small("c2", L=4300, n_q=33, h=3, k=90), True),
     # handed to the two-call path: few queries, short cache, fp32, k above the list limit
     "bf16_decode": (small("c1", n_seq=3, L=5000, k=300), True),
     "bf16_shortL": (small("c2", L=3000, n_q=40, k=200), True),
@@ -157,6 +159,21 @@ def test_select_repairs_rows_with_misleading_samples(misa, sampled_are):
     assert torch.equal(val, ref_val)
     assert int(one_call.repaired.sum()) == wl.n_seq * wl.n_q     # every row took the repair pass
     check_against_oracle(inp, heads, idx, val, wl.k, [(0, 0), (0, 19)])
+
+
+def test_select_longest_rows(misa):
+    # the longest supported cache: bitmap and prefix arrays of the row kernel at their largest
+    wl = small("c2", L=524288, n_q=8, k=1000, needles=8)
+    inp = WL.make_inputs(wl, seed=8)
+    dv = misa.to_device(inp)
+    p = dv["problem"]
+    heads = random_heads(wl)
+    idx, val = one_call(misa, p, dv, heads, wl.k)
+    ref_idx, ref_val = two_call(misa, p, dv, heads, wl.k)
+    assert torch.equal(idx, ref_idx)
+    assert torch.equal(val, ref_val)
+    assert int(one_call.repaired.sum()) == 0
+    check_against_oracle(inp, heads, idx, val, wl.k, [(0, 7)])
 
 
 def test_select_ties_take_the_lower_index(misa):

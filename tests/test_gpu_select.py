@@ -176,6 +176,28 @@ def test_select_longest_rows(misa):
     check_against_oracle(inp, heads, idx, val, wl.k, [(0, 7)])
 
 
+@pytest.mark.parametrize("name", ["c2", "c4"])
+def test_select_full_size_workloads(misa, name):
+    # The prefill workloads at their full size, as bench.py --fused runs them: every row of the
+    # fused call equals the two-call path bit for bit and no row needed the repair pass; a few
+    # rows are also checked against the oracle.
+    wl = WL.WORKLOADS[name]
+    k = wl.k_cand if wl.k_cand else wl.k
+    inp = WL.make_inputs(wl)
+    dv = misa.to_device(inp)
+    p = dv["problem"]
+    ix = misa.Indexer(p, k)
+    ix.pool(dv["K"], dv["kscale"])
+    ix.route(dv["Q"], dv["W"], dv["K"], dv["kscale"])
+    idx, val = one_call(misa, p, dv, ix.heads, k)
+    ref_idx, ref_val = two_call(misa, p, dv, ix.heads, k)
+    assert torch.equal(idx, ref_idx)
+    assert torch.equal(val, ref_val)
+    assert int(one_call.repaired.sum()) == 0
+    del ref_idx, ref_val
+    check_against_oracle(inp, ix.heads, idx, val, k, [(0, 0), (0, wl.n_q // 2), (0, wl.n_q - 1)])
+
+
 def test_select_ties_take_the_lower_index(misa):
     # Many identical keys: equal scores everywhere, so the choice is decided by the index rule alone.
     wl = small("c2", L=8192, n_q=16, k=700)

@@ -12,6 +12,15 @@
  *   misa_topk          Eq. misa_topk/misa_candidate    top-k token selection
  *   misa_rerank        Eq. misa_final_topk             dense re-rank (MISA-dagger)
  *
+ * and, built from the same stages:
+ *
+ *   misa_select_tokens        scoring + top-k in one call, no score matrix
+ *   misa_pool_keys_update     pooled keys maintained after tokens are appended
+ *   misa_route_heads_proxy    the two content-free router scores of the
+ *                             routing-score ablation
+ *   misa_hisa_select,         the HISA and Block-Sparse comparison indexers
+ *   misa_block_sparse_select
+ *
  * Conventions common to all calls
  * -------------------------------
  * - Every data pointer is DEVICE memory owned by the caller unless it is
@@ -28,7 +37,7 @@
  *                                        scales must be finite and >= 0
  *     queries Q      [n_seq, n_q, H, d]  q_dtype
  *     gates   W      [n_seq, n_q, H]     float (any sign)
- *   K, Q must be 16-byte aligned.
+ *   K, Q (and Kp where it is an input) must be 16-byte aligned.
  * - Causality: query t of sequence i sees the keys 0 .. n-1 with
  *     len_i = seq_len ? clamp(seq_len[i], 0, L) : L
  *     n     = q_pos  ? clamp(q_pos[t] + 1, 0, len_i) : len_i

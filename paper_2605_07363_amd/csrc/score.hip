@@ -827,9 +827,12 @@ static hipError_t launch_stream(const Prob& p, const void* Q, const float* W, co
                                 const void* K, const float* kscale, float* S, hipStream_t st) {
   const int hc = heads ? p.h : p.H;
   const int nt = (hc + 15) / 16;
-  // 4 pipeline steps of one 64-key group per wavefront: 1024 keys per workgroup
-  // (measured best of 512 .. 4096 on MI355X for both bf16 and fp8 keys).
-  constexpr int STEPS = 4, G = 1, KPW = 256 * STEPS * G;
+  // bf16 keys: 4 pipeline steps of one 64-key group per wavefront, 1024 keys (256 KB) per
+  // workgroup.  fp8 keys: one step, 256 keys (32 KB) per workgroup - every wavefront loads
+  // its 8 KB, computes and retires, and latency is hidden by the other resident wavefronts
+  // alone.  Measured best of 256 .. 4096 keys per workgroup on MI355X for each type (fp8:
+  // 96 us against 102 us with 1024 keys; bf16: 94 us against 97 us with 256 keys).
+  constexpr int STEPS = KDT == MISA_FP8_E4M3 ? 1 : 4, G = 1, KPW = 256 * STEPS * G;
   const dim3 grid((p.L + KPW - 1) / KPW, p.n_q, p.n_seq);
   const uint16_t* q = static_cast<const uint16_t*>(Q);
 #define GO(NT) score_stream_kernel<KDT, NT, STEPS, G><<<grid, 256, 0, st>>>(p, q, W, heads, K, kscale, S)

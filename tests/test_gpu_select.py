@@ -39,6 +39,8 @@ CASES = {
     "fp8_dense64": (small("c4", L=4200, n_q=19, k=128, k_cand=0, needles=8), False),
     "bf16_bigk": (small("c2", L=20000, n_q=33, k=8192), True),
     "bf16_k1": (small("c2", L=4100, n_q=9, k=1), True),
+    # few long rows: the two-call reference takes the split top-k path here
+    "fp8_fewrows": (small("c4", L=40000, n_q=16, k=700, k_cand=0, needles=16), True),
     "fp8_h32": (small("c4", L=4800, n_q=11, h=32, k=150, k_cand=0, needles=8), True),
     "bf16_h3": (small("c2", L=4300, n_q=33, h=3, k=90), True),
     # handed to the two-call path: few queries, short cache, fp32, k above the list limit

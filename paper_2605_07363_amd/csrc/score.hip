@@ -828,19 +828,27 @@ static hipError_t launch_stream(const Prob& p, const void* Q, const float* W, co
   const int hc = heads ? p.h : p.H;
   const int nt = (hc + 15) / 16;
   // bf16 keys: 4 pipeline steps of one 64-key group per wavefront, 1024 keys (256 KB) per
-  // workgroup.  fp8 keys: one step, 256 keys (32 KB) per workgroup - every wavefront loads
-  // its 8 KB, computes and retires, and latency is hidden by the other resident wavefronts
-  // alone.  Measured best of 256 .. 4096 keys per workgroup on MI355X for each type (fp8:
-  // 96 us against 102 us with 1024 keys; bf16: 94 us against 97 us with 256 keys).
-  constexpr int STEPS = KDT == MISA_FP8_E4M3 ? 1 : 4, G = 1, KPW = 256 * STEPS * G;
-  const dim3 grid((p.L + KPW - 1) / KPW, p.n_q, p.n_seq);
+  // workgroup.  fp8 keys with up to 16 heads: one step, 256 keys (32 KB) per workgroup -
+  // every wavefront loads its 8 KB, computes and retires, and latency is hidden by the
+  // other resident wavefronts alone (4 per SIMD).  Measured best of 256 .. 4096 keys per
+  // workgroup on MI355X for each type (fp8: 96 us against 102 us with 1024 keys; bf16: 94 us
+  // against 97 us with 256 keys); with more head tiles fewer wavefronts fit a SIMD and the
+  // pipelined form is faster again (32 heads, fp8: 105 us against 134 us).
   const uint16_t* q = static_cast<const uint16_t*>(Q);
-#define GO(NT) score_stream_kernel<KDT, NT, STEPS, G><<<grid, 256, 0, st>>>(p, q, W, heads, K, kscale, S)
+#define GO(NT, STEPS)                                                                             \
+  do {                                                                                            \
+    constexpr int KPW = 256 * (STEPS);                                                            \
+    const dim3 grid((p.L + KPW - 1) / KPW, p.n_q, p.n_seq);                                       \
+    score_stream_kernel<KDT, NT, STEPS, 1><<<grid, 256, 0, st>>>(p, q, W, heads, K, kscale, S);   \
+  } while (0)
   switch (nt) {
-    case 1: GO(1); break;
-    case 2: GO(2); break;
-    case 3: GO(3); break;
-    default: GO(4); break;
+    case 1:
+      if (KDT == MISA_FP8_E4M3) GO(1, 1);
+      else GO(1, 4);
+      break;
+    case 2: GO(2, 4); break;
+    case 3: GO(3, 4); break;
+    default: GO(4, 4); break;
   }
 #undef GO
   return hipGetLastError();

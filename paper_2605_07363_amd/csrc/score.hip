@@ -266,7 +266,7 @@ __global__ __launch_bounds__(256) void score_stream_kernel(
 //   of keys.  Each wavefront keeps the gathered head rows of its own queries
 //   in registers for the whole key range (the query operand is stationary),
 //   while 64-key tiles stream through LDS, double buffered, widened to bf16
-//   once when they are staged and XOR-swizzled so that fragment reads are
+//   once when they are staged, rows padded by one 16-byte slot so that fragment reads are
 //   free of bank conflicts.  Head rows are placed so that all active heads of
 //   a query fall into accumulator registers of the same lane: a lane of the
 //   lower half-wave holds rows {0-3, 8-11, 16-19, 24-27} of a 32-row tile,
@@ -296,6 +296,7 @@ struct TileGeom {
 };
 
 constexpr int kKT = 64;  // keys per LDS tile
+constexpr int kKP = 17;  // 16-byte slots per key row in LDS: 16 of data + 1 of padding
 // Queries per sequence from which the tiled matrix-core kernel is used.
 constexpr int kTileMinQueries = 8;
 constexpr int kStageCap = 256;  // filter mode: staged candidates per wavefront and pair of queries
@@ -324,7 +325,7 @@ __device__ __forceinline__ void score_tile_body(
   constexpr int NQL_ = HS == 8 ? RT * 2 : (HS == 16 ? RT : 1);  // queries per lane
   constexpr int ROW_BYTES = KDT == MISA_BF16 ? 256 : 128;
   constexpr int NLD = KDT == MISA_BF16 ? 4 : 2;  // 16-byte global loads per thread and tile
-  __shared__ uint4 ktile[2][kKT * 16];
+  __shared__ uint4 ktile[2][kKT * kKP];
   __shared__ float kscl[2][kKT];
   __shared__ int nvis[QWG];
   __shared__ int s_head[QWG][HS];
@@ -405,18 +406,18 @@ __device__ __forceinline__ void score_tile_body(
     }                                                                                             \
     if (KDT == MISA_FP8_E4M3 && tid < kKT) st_scale = kscale[(size_t)seq * p.L + key_row((k0) + tid)]; \
   } while (0)
-  auto put_chunk = [&](int b, int chunk, const uint4& v) {  // registers -> LDS, bf16, XOR (row & 15)
+  auto put_chunk = [&](int b, int chunk, const uint4& v) {  // registers -> LDS, bf16, padded rows
     const int row = chunk / CPR, c = chunk % CPR;
     if (KDT == MISA_BF16) {
-      ktile[b][row * 16 + (c ^ (row & 15))] = v;
+      ktile[b][row * kKP + c] = v;
     } else {
       uint4 lo, hi;
       fp8x4_to_bf16x4(v.x, lo.x, lo.y);
       fp8x4_to_bf16x4(v.y, lo.z, lo.w);
       fp8x4_to_bf16x4(v.z, hi.x, hi.y);
       fp8x4_to_bf16x4(v.w, hi.z, hi.w);
-      ktile[b][row * 16 + ((2 * c) ^ (row & 15))] = lo;
-      ktile[b][row * 16 + ((2 * c + 1) ^ (row & 15))] = hi;
+      ktile[b][row * kKP + 2 * c] = lo;
+      ktile[b][row * kKP + 2 * c + 1] = hi;
     }
   };
 #define MISA_TILE_STORE(b)                                        \
@@ -492,16 +493,15 @@ __device__ __forceinline__ void score_tile_body(
   // workgroup, all of which exist: no masks are needed there
   const int plain_end = min(n_min, k_end);
 
-  // LDS fragment positions of this lane (16-byte units): row col of column tile 0, chunk
-  // (2 ks + hf) XOR-swizzled by the row, i.e. frag0 ^ (2 ks); the other column tile is 32
-  // rows further.  Only frag0 is kept; the XOR is applied to frag0 + tile offset (whose low
-  // four bits are zero) at every use, which costs nothing and frees seven registers.
-  const int frag0 = col * 16 + (hf ^ (col & 15));
+  // LDS fragment position of this lane (16-byte units): row col of column tile 0, chunk
+  // 2 ks + hf.  Rows are 17 slots apart, so the 16 lanes that read together hit 16 different
+  // bank groups, and the k-step only adds a constant: one address register per step.
+  const int frag0 = col * kKP + hf;
   // One 32-key column tile: eight fragment reads, 8 x RT MFMAs.
-  auto mfma_tile = [&](f32x16 (&acc)[RT], int tile) {  // tile: buffer * 1024 + column tile * 512
+  auto mfma_tile = [&](f32x16 (&acc)[RT], int tile) {  // tile: (buffer * 64 + column tile * 32) * kKP
     Frag b[8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) b[ks].u = (&ktile[0][0])[(frag0 + tile) ^ (2 * ks)];
+    for (int ks = 0; ks < 8; ++ks) b[ks].u = (&ktile[0][0])[frag0 + tile + 2 * ks];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
@@ -564,7 +564,7 @@ __device__ __forceinline__ void score_tile_body(
                        const f32x16 (&acc_old)[RT], int key, float scale) {
     Frag b[8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) b[ks].u = (&ktile[0][0])[(frag0 + tile) ^ (2 * ks)];
+    for (int ks = 0; ks < 8; ++ks) b[ks].u = (&ktile[0][0])[frag0 + tile + 2 * ks];
     float out[NQL];
 #pragma unroll
     for (int j = 0; j < NQL; ++j) out[j] = 0.f;
@@ -629,15 +629,15 @@ __device__ __forceinline__ void score_tile_body(
     auto body = [&](auto tag, int i) {
       const int buf = i & 1, k0 = k_begin + i * kKT;
       const bool more = i + 1 < n_tiles;
-      if (FILTER) loose_step(tag, accB, buf * 1024 + 512, accA, k0 + col, scaleA);
-      else tile_step(tag, accB, buf * 1024 + 512, accA, k0 + col, scaleA);
+      if (FILTER) loose_step(tag, accB, (buf * 64 + 32) * kKP, accA, k0 + col, scaleA);
+      else tile_step(tag, accB, (buf * 64 + 32) * kKP, accA, k0 + col, scaleA);
       if (KDT == MISA_FP8_E4M3) scaleB = kscl[buf][32 + col];
       if (more) MISA_TILE_STORE(buf ^ 1);
       __syncthreads();
       if (more) {
         if (i + 2 < n_tiles) MISA_TILE_LOAD(k0 + 2 * kKT);
-        if (FILTER) loose_step(tag, accA, (buf ^ 1) * 1024, accB, k0 + 32 + col, scaleB);
-        else tile_step(tag, accA, (buf ^ 1) * 1024, accB, k0 + 32 + col, scaleB);
+        if (FILTER) loose_step(tag, accA, (buf ^ 1) * 64 * kKP, accB, k0 + 32 + col, scaleB);
+        else tile_step(tag, accA, (buf ^ 1) * 64 * kKP, accB, k0 + 32 + col, scaleB);
         if (KDT == MISA_FP8_E4M3) scaleA = kscl[buf ^ 1][col];
       } else {
         epilogue(tag, accB, k0 + 32 + col, scaleB);

@@ -98,28 +98,49 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 }
 constexpr uint32_t kKeyNegInf = 0x007FFFFFu;  // order_key(-inf)
 
+// Inclusive prefix sum inside each row of 16 lanes: four shifted adds (data-parallel-primitive
+// moves with zero shifted in).  All lanes of the wavefront must be active.
+__device__ __forceinline__ int row16_inclusive_scan(int v) {
+  int x = v;
+  x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, true);  // row_shr:1
+  x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, true);  // row_shr:2
+  x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, true);  // row_shr:4
+  x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, true);  // row_shr:8
+  return x;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wavefront, all of them active: the row scans,
+// then the totals of the rows before a lane's own are added from lanes 15, 31 and 47.
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  const int x = row16_inclusive_scan(v);
+  const int t0 = __builtin_amdgcn_readlane(x, 15);
+  const int t1 = __builtin_amdgcn_readlane(x, 31);
+  const int t2 = __builtin_amdgcn_readlane(x, 47);
+  const int lane = threadIdx.x & 63;
+  return x + (lane >= 16 ? t0 : 0) + (lane >= 32 ? t1 : 0) + (lane >= 48 ? t2 : 0);
+}
+
+// Given the totals of the block's wavefronts in wave_total[0 .. nw-1] (nw <= 16), returns the
+// sum of the totals of the wavefronts before this one and, in *total, the sum of all: the
+// first 16 lanes of every wavefront read one total each and scan them.
+__device__ __forceinline__ int waves_before(const int* wave_total, int nw, int* total) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int x = row16_inclusive_scan(lane < nw ? wave_total[lane] : 0);
+  *total = __builtin_amdgcn_readlane(x, 15);
+  return wave > 0 ? __builtin_amdgcn_readlane(x, wave - 1) : 0;
+}
+
 // Exclusive prefix sum over a 1-D thread block (blockDim.x a multiple of 64,
-// at most 1024).  `scratch` holds 17 ints of LDS.  Also returns the block
+// at most 1024).  `scratch` holds 16 ints of LDS.  Also returns the block
 // total in *total.  Contains two barriers.
 __device__ __forceinline__ int block_exclusive_scan(int v, int* scratch, int* total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  int inc = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int y = __shfl_up(inc, o);
-    if (lane >= o) inc += y;
-  }
+  const int inc = wave_inclusive_scan(v);
   __syncthreads();  // scratch may still be read from a previous call
   if (lane == 63) scratch[wave] = inc;
   __syncthreads();
-  int base = 0, tot = 0;
-  for (int w = 0; w < nw; ++w) {
-    const int c = scratch[w];
-    if (w < wave) base += c;
-    tot += c;
-  }
-  *total = tot;
-  return base + inc - v;
+  return waves_before(scratch, nw, total) + inc - v;
 }
 
 }  // namespace misa

@@ -11,18 +11,25 @@ constexpr int kTopkThreads = 1024;
 constexpr int kBins = 2048;
 
 // Finds the digit d (scanning from the top) with count(digit > d) < need <= count(digit >= d).
-// A block of NT threads; thread i owns the 2048 / NT bins from 2047 - i * 2048 / NT downwards.
-// Writes {d, need - count(digit > d), hist[d]} to out.
+// A block of NT threads, the histogram complete; thread i owns the 2048 / NT bins from
+// 2047 - i * 2048 / NT downwards.  Writes {d, need - count(digit > d), hist[d]} to out
+// (nothing if need exceeds the total).  Uses scan_scratch[16..31] (block_exclusive_scan uses
+// the lower half); two barriers, the second at the end.
 template <int NT>
 __device__ __forceinline__ void find_threshold_bin_n(const int* hist, int need, int* scan_scratch,
                                                      int* out) {
-  constexpr int BPT = kBins / NT;
+  constexpr int BPT = kBins / NT, NW = NT / 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int top = kBins - 1 - BPT * (int)threadIdx.x;
+  int* wave_total = scan_scratch + 16;
   int h[BPT], sum = 0;
 #pragma unroll
   for (int i = 0; i < BPT; ++i) { h[i] = hist[top - i]; sum += h[i]; }
+  const int inc = wave_inclusive_scan(sum);
+  if (lane == 63) wave_total[wave] = inc;
+  __syncthreads();
   int total;
-  int above = block_exclusive_scan(sum, scan_scratch, &total);
+  int above = waves_before(wave_total, NW, &total) + inc - sum;
 #pragma unroll
   for (int i = 0; i < BPT; ++i) {
     if (above < need && need <= above + h[i]) {

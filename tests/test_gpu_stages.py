@@ -44,6 +44,11 @@ CASES = {
     "fp8_prefill_h32": small("c4", L=1100, n_q=13, h=32, B=32, k=64, k_cand=256, needles=8),
     "bf16_prefill_h3": small("c2", L=900, n_q=33, h=3, B=16, k=50),
     "bf16_decode_H1": WL.scaled(WL.WORKLOADS["c1"], n_seq=2, L=700, H=1, h=1, B=8, k=20, needles=2),
+    # decode batches of eight sequences and more: routing runs as one workgroup per sequence
+    # (fewer pooled-block tiles than wavefronts / several tiles per wavefront / a single head)
+    "bf16_decode_batch": small("c1", n_seq=9, L=2600, B=16, k=100, needles=8),
+    "fp8_decode_batch": small("c3", n_seq=8, L=9000, B=8, k=100, needles=8),
+    "bf16_decode_batch_H1": WL.scaled(WL.WORKLOADS["c1"], n_seq=8, L=500, H=1, h=1, B=4, k=20, needles=2),
 }
 
 
@@ -279,7 +284,7 @@ def test_topk_negative_and_extreme_values(misa):
 
 
 def test_topk_long_rows_split_over_workgroups(misa):
-    # few long rows take the multi-workgroup path (histogram + partition + finish)
+    # few long rows take the multi-workgroup path (sampled prefilter + exact finish)
     rng = np.random.default_rng(25)
     S = rng.standard_normal((2, 2, 40000)).astype(np.float32)
     q_pos = np.array([39999, 33333], dtype=np.int32)
@@ -288,6 +293,35 @@ def test_topk_long_rows_split_over_workgroups(misa):
     _topk_case(misa, S, 2048, q_pos=q_pos, seq_len=np.array([40000, 35000], dtype=np.int32))
     # decode rows whose visible prefix is not longer than k: everything is selected
     _topk_case(misa, np.ascontiguousarray(S[:, :1]), 16384, seq_len=np.array([10000, 16385], dtype=np.int32))
+
+
+def test_topk_prefilter_hand_over_cases(misa):
+    # Few long rows: several workgroups per row pass on the elements above a threshold taken
+    # from a sample of the row (one 16-element line out of every `ls`, chosen by a hash).  Rows
+    # built so that the hand-over is unusable must come out exact all the same.
+    rng = np.random.default_rng(29)
+    n_seq, L = 7, 65536
+    S = rng.standard_normal((n_seq, 1, L)).astype(np.float32)
+    S[1, 0] = np.sort(S[1, 0])                                  # every selected element in the last range
+    lines = L // 16
+    ls = -(-lines // 256)
+    g = np.arange(lines // ls, dtype=np.uint64)
+    sampled = (g * ls + (((g * 2654435761) & 0xFFFFFFFF) >> 16) % ls).astype(np.int64)
+    hot = np.zeros(lines, dtype=bool); hot[sampled] = True
+    row = -np.abs(S[2, 0]).reshape(lines, 16)                   # large values only where the sample looks:
+    row[hot] = 5.0 + rng.random((hot.sum(), 16))                # the threshold comes out too high
+    S[2, 0] = row.reshape(-1)
+    row = -np.abs(S[3, 0]).reshape(lines, 16)                   # ... and only where it does not look:
+    cold = np.flatnonzero(~hot)[:200]                           # more elements pass than the sample suggests
+    row[cold] = 5.0 + rng.random((cold.size, 16))
+    S[3, 0] = row.reshape(-1)
+    S[4, 0] = 0.5                                               # constant: everything passes
+    seq_len = np.array([L, L, L, L, L, 5000, 2048], dtype=np.int32)   # one short range; prefix == k
+    for k in (100, 2048, 6000):
+        _topk_case(misa, S, k, seq_len=seq_len)
+    # the same row lengths with causal positions instead of sequence lengths
+    S2 = np.ascontiguousarray(S[:1].repeat(3, axis=1))
+    _topk_case(misa, S2, 2048, q_pos=np.array([L - 1, 40000, 8191], dtype=np.int32))
 
 
 @pytest.mark.parametrize("shape", [(2, 1, 40000), (3, 300, 3000)])
@@ -310,8 +344,8 @@ def test_topk_tie_paths(misa, shape):
 
 
 def test_topk_sampled_single_read_path(misa):
-    # many long rows: the kernel brackets the threshold from a sample and reads the row
-    # once; rows built to defeat the sample must fall back and still be exact
+    # many long rows (one workgroup per row); rows with sorted, repeated, constant, clustered
+    # and -inf values
     rng = np.random.default_rng(28)
     rows, L = 264, 40000
     S = rng.standard_normal((1, rows, L)).astype(np.float32)

@@ -20,6 +20,8 @@
  *                             routing-score ablation
  *   misa_hisa_select,         the HISA and Block-Sparse comparison indexers
  *   misa_block_sparse_select
+ *   misa_probe_hbm_read,      achievable read and matrix rates of the machine,
+ *   misa_probe_mfma_bf16      for roofline reports
  *
  * Conventions common to all calls
  * -------------------------------
@@ -289,6 +291,27 @@ misa_status misa_hisa_select(const misa_problem* p, const void* Q, const float* 
 misa_status misa_block_sparse_select(const misa_problem* p, const void* Q, const float* W,
                                      const float* Kp, int32_t m, int32_t* blocks, int32_t* idx,
                                      void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Measurement probes (not part of the method; for callers that report rates against
+ * what the machine delivers as well as against its published peaks).
+ *
+ * misa_probe_hbm_read: one kernel that reads `bytes` bytes of `buf` once (short-lived
+ * wavefronts, every load issued up front: the fastest read pattern found on this chip)
+ * and writes nothing.  bytes / its duration is the achievable read rate.
+ *   buf    in   device, 16-byte aligned, bytes a positive multiple of 8192
+ *   sink   out  device, at least 1024 bytes (written only on a one-in-2^32 data match)
+ *
+ * misa_probe_mfma_bf16: `workgroups` workgroups of four wavefronts, each wavefront issuing
+ * iters x 4 independent v_mfma_f32_32x32x16_bf16 on register operands.  *flops / its
+ * duration is the achievable dense bf16 matrix rate at the clock the chip sustains.
+ *   sink   out  device, workgroups * 256 floats
+ *   flops  out  HOST pointer or NULL: floating-point operations of the launch
+ * Both enqueue on `stream` and return; time them with events.
+ */
+misa_status misa_probe_hbm_read(const void* buf, size_t bytes, void* sink, void* stream);
+misa_status misa_probe_mfma_bf16(int32_t workgroups, int32_t iters, float* sink, double* flops,
+                                 void* stream);
 
 #ifdef __cplusplus
 }

@@ -275,4 +275,23 @@ misa_status misa_rerank(const misa_problem* p, const void* Q, const float* W, co
                     "misa_rerank top-k launch");
 }
 
+misa_status misa_probe_hbm_read(const void* buf, size_t bytes, void* sink, void* stream) {
+  if (!buf || !sink) return fail(MISA_ERR_INVALID_ARG, "buf or sink is NULL");
+  if (!aligned(buf, 16)) return fail(MISA_ERR_INVALID_ARG, "buf must be 16-byte aligned");
+  if (bytes < 8192 || bytes % 8192 != 0 || bytes > ((size_t)1 << 40))
+    return fail(MISA_ERR_INVALID_ARG, "bytes must be a positive multiple of 8192 (got %zu)", bytes);
+  return hip_result(misa::launch_probe_read(buf, bytes, sink, (hipStream_t)stream),
+                    "misa_probe_hbm_read launch");
+}
+
+misa_status misa_probe_mfma_bf16(int32_t workgroups, int32_t iters, float* sink, double* flops,
+                                 void* stream) {
+  if (!sink) return fail(MISA_ERR_INVALID_ARG, "sink is NULL");
+  if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 24))
+    return fail(MISA_ERR_INVALID_ARG, "need 1 <= workgroups <= 2^20 and 1 <= iters <= 2^24");
+  if (flops) *flops = (double)workgroups * 4.0 * (double)iters * misa::kProbeMfmaFlopsPerWaveIter;
+  return hip_result(misa::launch_probe_mfma(workgroups, iters, sink, (hipStream_t)stream),
+                    "misa_probe_mfma_bf16 launch");
+}
+
 }  // extern "C"

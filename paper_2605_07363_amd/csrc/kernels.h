@@ -71,4 +71,9 @@ hipError_t launch_hisa(const Prob& p, int k_dtype, int q_dtype, const void* Q, c
                        const float* Kp, const void* K, const float* kscale, int m, int k, int* blocks,
                        int* idx, float* val, void* ws, hipStream_t st);
 
+// Probes for the roofline report (peaks.hip).
+constexpr int kProbeMfmaFlopsPerWaveIter = 4 * 2 * 32 * 32 * 16;
+hipError_t launch_probe_read(const void* buf, size_t bytes, void* sink, hipStream_t st);
+hipError_t launch_probe_mfma(int workgroups, int iters, float* sink, hipStream_t st);
+
 }  // namespace misa

@@ -71,13 +71,8 @@ __device__ __forceinline__ int wave_find_bin(const int* hist, int need, int* res
   const int top = kBins - 1 - 32 * lane;
   int local = 0;
 #pragma unroll
-  for (int i = 0; i < 32; ++i) local += hist[top - i];
-  int inc = local;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int y = __shfl_up(inc, o);
-    if (lane >= o) inc += y;
-  }
+  for (int i = 0; i < 32; ++i) local += hist[top - ((i + lane) & 31)];  // rotated: lanes on different banks
+  const int inc = wave_inclusive_scan(local);
   int above = inc - local;
   const bool mine = above < need && need <= inc;
   int d = 0, r = 0;

@@ -62,6 +62,10 @@ lib.misa_hisa_select.argtypes = [_P, _V, _V, _V, _V, _V, ctypes.c_int32, ctypes.
                                  ctypes.c_size_t, _V]
 lib.misa_block_sparse_select.restype = ctypes.c_int
 lib.misa_block_sparse_select.argtypes = [_P, _V, _V, _V, ctypes.c_int32, _V, _V, _V, ctypes.c_size_t, _V]
+lib.misa_probe_hbm_read.restype = ctypes.c_int
+lib.misa_probe_hbm_read.argtypes = [_V, ctypes.c_size_t, _V, _V]
+lib.misa_probe_mfma_bf16.restype = ctypes.c_int
+lib.misa_probe_mfma_bf16.argtypes = [ctypes.c_int32, ctypes.c_int32, _V, ctypes.POINTER(ctypes.c_double), _V]
 lib.misa_rerank.restype = ctypes.c_int
 lib.misa_rerank.argtypes = [_P, _V, _V, _V, _V, _V, ctypes.c_int32, ctypes.c_int32, _V, _V, _V,
                             ctypes.c_size_t, _V]
@@ -206,6 +210,46 @@ def block_sparse_select(p: Problem, Q, W, Kp, m: int, idx, blocks=None, ws=None)
     w, wb = _ws(ws)
     _check(lib.misa_block_sparse_select(ctypes.byref(p.c()), _ptr(Q), _ptr(W), _ptr(Kp), m, _ptr(blocks),
                                         _ptr(idx), w, wb, _stream()))
+
+
+def probe_hbm_read(buf, sink, nbytes: Optional[int] = None) -> int:
+    """Enqueues one read of the first nbytes bytes of buf (default: all, rounded down to 8 KiB); returns nbytes."""
+    total = buf.numel() * buf.element_size()
+    nbytes = (total if nbytes is None else min(nbytes, total)) // 8192 * 8192
+    _check(lib.misa_probe_hbm_read(_ptr(buf), nbytes, _ptr(sink), _stream()))
+    return nbytes
+
+
+def probe_mfma_bf16(workgroups: int, iters: int, sink) -> float:
+    """Enqueues the matrix-instruction probe; returns its floating-point operation count."""
+    if sink.numel() < workgroups * 256 or sink.dtype != torch.float32:
+        raise ValueError("sink must hold workgroups * 256 floats")
+    flops = ctypes.c_double(0.0)
+    _check(lib.misa_probe_mfma_bf16(workgroups, iters, _ptr(sink), ctypes.byref(flops), _stream()))
+    return flops.value
+
+
+def measured_peaks(device="cuda", repeats: int = 10) -> dict:
+    """Achievable HBM read rate (GB/s) and dense bf16 matrix rate (TFLOP/s) of this GPU, each the
+    best of `repeats` event-timed launches of the library's probes (512 MiB read; ~1e13 flop)."""
+    buf = torch.empty(512 << 20, dtype=torch.uint8, device=device)
+    buf.fill_(1)
+    sink = torch.zeros(8 * 1024 * 256, dtype=torch.float32, device=device)
+    cus = torch.cuda.get_device_properties(device).multi_processor_count
+    wgs, iters = cus * 8, 2048
+    out = {}
+    for name in ("hbm_read_GBps", "mfma_bf16_TFLOPs"):
+        best = float("inf")
+        amount = 0.0
+        for _ in range(repeats + 2):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            amount = probe_hbm_read(buf, sink) if name.startswith("hbm") else probe_mfma_bf16(wgs, iters, sink)
+            e1.record()
+            e1.synchronize()
+            best = min(best, e0.elapsed_time(e1))
+        out[name] = amount / (best * 1e-3) / (1e9 if name.startswith("hbm") else 1e12)
+    return out
 
 
 # ---------------------------------------------------------------------------

@@ -18,8 +18,9 @@ def misa():
 def test_every_declared_symbol_is_exported(misa):
     header = open(os.path.join(ROOT, "include", "misa.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    names = set(re.findall(r"\b(misa_[a-z_]+)\s*\(", header))
+    names = set(re.findall(r"\b(misa_[a-z0-9_]+)\s*\(", header))
     assert {"misa_pool_keys", "misa_route_heads", "misa_score_tokens", "misa_topk", "misa_rerank", "misa_select_tokens", "misa_hisa_select", "misa_block_sparse_select", "misa_pool_keys_update", "misa_route_heads_proxy",
+            "misa_probe_hbm_read", "misa_probe_mfma_bf16",
             "misa_workspace_bytes", "misa_last_error", "misa_version"} <= names
     for n in names:
         assert hasattr(misa.lib, n), f"{n} declared in misa.h but not exported"

@@ -441,3 +441,17 @@ def test_run_twice_bit_identical(misa):
         outs.append([x.clone() for x in (ix.Kp, ix.heads, ix.E, ix.S, ix.idx1, ix.idx, ix.val)])
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+
+
+# --------------------------------------------------------------------- measurement probes
+def test_measurement_probes_report_plausible_rates(misa):
+    peaks = misa.measured_peaks(repeats=3)
+    assert 2000.0 < peaks["hbm_read_GBps"] < 8000.0          # below the published 8 TB/s, above any cache-less floor
+    assert 500.0 < peaks["mfma_bf16_TFLOPs"] < 2600.0        # below the published 2.5 PFLOP/s dense bf16
+    sink = torch.zeros(256, dtype=torch.float32, device="cuda")
+    flops = misa.probe_mfma_bf16(1, 3, sink)
+    torch.cuda.synchronize()
+    assert flops == 4 * 3 * 4 * 2 * 32 * 32 * 16
+    # operands are 1.0 x {0.5, 1.0}: every accumulator element is 3 iterations x 16 products
+    got = sink.cpu().numpy()
+    assert set(np.unique(got).tolist()) <= {4 * 16 * 3 * 16 * 0.5, 4 * 16 * 3 * 16 * 1.0, 4 * 16 * 3 * 16 * 0.75}

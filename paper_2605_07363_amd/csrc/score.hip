@@ -794,21 +794,24 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
     if (hf == 0 && slot < c_end) orow[slot] = r.s >= 0 ? sum * r.scale : -INFINITY;
   };
 
-  Raw bufA, bufB;
+  // kDepth register buffers: the loads of a step are issued kDepth - 1 steps before they are
+  // used (a step of one wavefront is far shorter than the latency of a gathered row).
+  constexpr int kDepth = KDT == MISA_BF16 ? 3 : 4;
+  Raw buf[kDepth];
   int c0 = c_begin + wave * 32;
   __builtin_amdgcn_s_waitcnt(0);  // the query operand has landed; in-loop waits concern only loop loads
   __syncthreads();                // candidate indices are in LDS
-  issue(bufA, c0);
-  while (c0 < c_end) {
-    issue(bufB, c0 + 128);
-    __builtin_amdgcn_sched_barrier(0);
-    finish(bufA, c0);
-    c0 += 128;
-    if (c0 >= c_end) break;
-    issue(bufA, c0 + 128);
-    __builtin_amdgcn_sched_barrier(0);
-    finish(bufB, c0);
-    c0 += 128;
+#pragma unroll
+  for (int d = 0; d < kDepth - 1; ++d) issue(buf[d], c0 + 128 * d);
+  while (true) {
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+      issue(buf[(d + kDepth - 1) % kDepth], c0 + 128 * (kDepth - 1));
+      __builtin_amdgcn_sched_barrier(0);
+      finish(buf[d], c0);
+      c0 += 128;
+      if (c0 >= c_end) return;
+    }
   }
 }
 

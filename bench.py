@@ -86,6 +86,8 @@ def main() -> int:
     ap.add_argument("--incremental-pool", action="store_true",
                     help="decode workloads: the pooled keys of earlier tokens are kept and a step only re-pools "
                          "the block of the newest token (misa_pool_keys_update), as a serving loop would")
+    ap.add_argument("--paged", type=int, default=0, metavar="PAGE_SIZE",
+                    help="keep the key cache as a pool of scattered pages of PAGE_SIZE tokens (misa_problem.page_table)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate", type=int, default=3, help="key-cache copies rotated between steps (cold reads)")
     ap.add_argument("--no-graph", action="store_true",
@@ -109,9 +111,11 @@ def main() -> int:
     torch.cuda.set_device(0)
     inp = WL.make_inputs(wl)
     dv = misa.to_device(inp)
+    key_bytes = dv["K"].numel() * dv["K"].element_size()
+    if args.paged:
+        dv = misa.paginate(dv, args.paged, seed=1)
     p = dv["problem"]
     Q, W = dv["Q"], dv["W"]
-    key_bytes = dv["K"].numel() * dv["K"].element_size()
     # Decode caches are far larger than the 256 MB last-level cache; rotating
     # copies keeps every step's key reads cold.  Prefill caches are small and
     # are re-read by every query tile, so one copy is the workload.
@@ -243,7 +247,9 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32" if wl.k_dtype == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {DESCRIPTIONS[wl.name]}"
-                               + (f" [overridden: {override}]" if override else ""), "pairs_per_step": pairs,
+                               + (f" [overridden: {override}]" if override else "")
+                               + (f" [key cache in pages of {args.paged} tokens]" if args.paged else ""),
+                   "pairs_per_step": pairs,
                    "key_cache_bytes": key_bytes, "key_buffers_rotated": n_rot},
         "launch": "hip-graph replay of the whole step" if use_graph else "eager",
         "eager_ms_per_step": eager_ms,

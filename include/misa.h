@@ -111,6 +111,16 @@ typedef struct misa_problem {
   const int32_t* q_pos;   /* device [n_q], shared by all sequences; NULL = decode:
                              every query sits at the last position (n = len_i)       */
   const int32_t* seq_len; /* device [n_seq] or NULL (every sequence holds L keys)     */
+  /* Paged key cache (optional; all three zero / NULL = contiguous K [n_seq, L, d]).
+   * With a page table K is a pool of pages [n_pages, page_size, d] and kscale
+   * [n_pages, page_size]; key s of sequence i is row
+   *   page_table[i * max_pages + s / page_size] * page_size + s % page_size
+   * of the pool.  Only entries for pages that hold keys 0 .. L-1 are read; they
+   * must name pages inside the pool (not checked).  Every K / kscale argument of
+   * every call is then the pool; S, Kp, indices and candidates stay logical.    */
+  const int32_t* page_table; /* device [n_seq, max_pages] or NULL                      */
+  int32_t page_size;         /* tokens per page: a power of two, 16 .. 65536           */
+  int32_t max_pages;         /* row length of page_table, >= ceil(L / page_size)       */
 } misa_problem;
 
 /* Bytes of scratch the given op needs for this problem.  `k` is the k of

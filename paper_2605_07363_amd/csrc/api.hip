@@ -45,6 +45,20 @@ misa_status check_problem(const misa_problem* p, misa::Prob* out) {
   out->h = p->h;
   out->M = (int)(((long long)p->L + p->B - 1) / p->B);
   out->q_pos = p->q_pos; out->seq_len = p->seq_len;
+  out->page_table = nullptr; out->page_shift = 0; out->max_pages = 0;
+  if (p->page_table) {
+    const int ps = p->page_size;
+    if (ps < 16 || ps > 65536 || (ps & (ps - 1)) != 0)
+      return fail(MISA_ERR_INVALID_ARG, "page_size must be a power of two in 16..65536 (got %d)", ps);
+    if ((long long)p->max_pages * ps < p->L)
+      return fail(MISA_ERR_INVALID_ARG, "max_pages * page_size must cover L (max_pages=%d, page_size=%d, L=%d)",
+                  p->max_pages, ps, p->L);
+    out->page_table = p->page_table;
+    out->max_pages = p->max_pages;
+    while ((1 << out->page_shift) < ps) ++out->page_shift;
+  } else if (p->page_size != 0 || p->max_pages != 0) {
+    return fail(MISA_ERR_INVALID_ARG, "page_size / max_pages given without a page_table");
+  }
   return MISA_OK;
 }
 

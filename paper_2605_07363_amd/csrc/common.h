@@ -22,7 +22,20 @@ struct Prob {
   int n_seq, L, n_q, H, B, h, M;
   const int* q_pos;
   const int* seq_len;
+  const int* page_table;   // nullptr: keys contiguous per sequence
+  int page_shift, max_pages;
 };
+
+// Row of key s of sequence seq in the key array (contiguous cache or page pool).
+template <bool PAGED>
+__device__ __forceinline__ size_t key_slot(const Prob& p, int seq, int s) {
+  if (!PAGED) return (size_t)seq * p.L + s;
+  const int page = p.page_table[(size_t)seq * p.max_pages + (s >> p.page_shift)];
+  return ((size_t)page << p.page_shift) + (s & ((1 << p.page_shift) - 1));
+}
+__device__ __forceinline__ size_t key_slot(const Prob& p, int seq, int s) {
+  return p.page_table ? key_slot<true>(p, seq, s) : key_slot<false>(p, seq, s);
+}
 
 __device__ __forceinline__ int seq_length(const Prob& p, int seq) {
   int len = p.L;

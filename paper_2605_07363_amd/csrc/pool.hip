@@ -23,7 +23,7 @@ constexpr int kPoolSplitFrom = 2048;  // blocks longer than this are sliced
 // from_token == nullptr: blockIdx.x / slices is the block.  Otherwise (update after tokens were
 // appended) it counts from the block that holds token from_token[seq], and blocks past the
 // sequence end are left alone.
-template <int DT>
+template <int DT, bool PAGED>
 __global__ __launch_bounds__(256) void pool_kernel(Prob p, int slices, const int* __restrict__ from_token,
                                                    const void* __restrict__ K,
                                                    const float* __restrict__ kscale,
@@ -51,14 +51,39 @@ __global__ __launch_bounds__(256) void pool_kernel(Prob p, int slices, const int
 #pragma unroll
   for (int e = 0; e < N; ++e) acc[e] = 0.f;
 
-  const char* base = static_cast<const char*>(K) + (size_t)seq * p.L * V::ROW_BYTES;
-  for (long long row = lo + r; row < hi; row += RPP) {
-    float v[N];
-    V::load(base + (size_t)row * V::ROW_BYTES + c * 16, v);
-    float s = 1.f;
-    if (DT == MISA_FP8_E4M3) s = kscale[(size_t)seq * p.L + row];
+  const char* base = static_cast<const char*>(K);
+  if (PAGED) {
+    // four rows per round: their page-table entries, then their keys, are in flight together
+    // (rows past the end are clamped and masked; the order of the additions is unchanged)
+    for (long long row0 = lo + r; row0 < hi; row0 += 4 * RPP) {
+      size_t slot[4];
+      float v[4][N], s[4];
 #pragma unroll
-    for (int e = 0; e < N; ++e) acc[e] = fmaf(v[e], s, acc[e]);
+      for (int u = 0; u < 4; ++u) slot[u] = key_slot<true>(p, seq, (int)min(row0 + u * RPP, hi - 1));
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        V::load(base + slot[u] * V::ROW_BYTES + c * 16, v[u]);
+        s[u] = 1.f;
+        if (DT == MISA_FP8_E4M3) s[u] = kscale[slot[u]];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (row0 + u * RPP < hi) {
+#pragma unroll
+          for (int e = 0; e < N; ++e) acc[e] = fmaf(v[u][e], s[u], acc[e]);
+        }
+      }
+    }
+  } else {
+    for (long long row = lo + r; row < hi; row += RPP) {
+      float v[N];
+      const size_t slot = key_slot<false>(p, seq, (int)row);
+      V::load(base + slot * V::ROW_BYTES + c * 16, v);
+      float s = 1.f;
+      if (DT == MISA_FP8_E4M3) s = kscale[slot];
+#pragma unroll
+      for (int e = 0; e < N; ++e) acc[e] = fmaf(v[e], s, acc[e]);
+    }
   }
 #pragma unroll
   for (int e = 0; e < N; ++e) red[r][c * N + e] = acc[e];
@@ -122,11 +147,15 @@ hipError_t launch_pool(const Prob& p, int k_dtype, const void* K, const float* k
   const int nb = from_token ? std::min(max_blocks, p.M) : p.M;
   const dim3 grid(nb * sl, p.n_seq), block(256);
   float* dst = sl == 1 ? Kp : static_cast<float*>(ws);
+#define GO(DT)                                                                                   \
+  if (p.page_table) pool_kernel<DT, true><<<grid, block, 0, st>>>(p, sl, from_token, K, kscale, dst); \
+  else pool_kernel<DT, false><<<grid, block, 0, st>>>(p, sl, from_token, K, kscale, dst)
   switch (k_dtype) {
-    case MISA_F32: pool_kernel<MISA_F32><<<grid, block, 0, st>>>(p, sl, from_token, K, kscale, dst); break;
-    case MISA_BF16: pool_kernel<MISA_BF16><<<grid, block, 0, st>>>(p, sl, from_token, K, kscale, dst); break;
-    default: pool_kernel<MISA_FP8_E4M3><<<grid, block, 0, st>>>(p, sl, from_token, K, kscale, dst); break;
+    case MISA_F32: GO(MISA_F32); break;
+    case MISA_BF16: GO(MISA_BF16); break;
+    default: GO(MISA_FP8_E4M3); break;
   }
+#undef GO
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || sl == 1) return e;
   pool_combine_kernel<<<dim3(nb, p.n_seq), 1024, 0, st>>>(p, sl, from_token, dst, Kp);

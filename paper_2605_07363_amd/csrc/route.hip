@@ -368,14 +368,15 @@ __global__ __launch_bounds__(128) void route_finalize_kernel(
   const bool tail = r > 0 && n < len;
 
   if (tail) {  // mean of keys nfull*B .. n-1, component tid
-    const char* base = static_cast<const char*>(K) + (size_t)seq * p.L * KV::ROW_BYTES;
+    const char* base = static_cast<const char*>(K);
     auto key_component = [&](int row) {
-      const char* src = base + (size_t)row * KV::ROW_BYTES;
+      const size_t slot = key_slot(p, seq, row);
+      const char* src = base + slot * KV::ROW_BYTES;
       if (KDT == MISA_F32) return reinterpret_cast<const float*>(src)[tid];
       if (KDT == MISA_BF16) return bf16_bits_to_float(reinterpret_cast<const uint16_t*>(src)[tid]);
       const uint32_t w = reinterpret_cast<const uint32_t*>(src)[tid >> 2];
       const f32x2 pr = __builtin_amdgcn_cvt_pk_f32_fp8(w >> ((tid & 2) * 8), false);
-      return pr[tid & 1] * kscale[(size_t)seq * p.L + row];
+      return pr[tid & 1] * kscale[slot];
     };
     // rows are added in order; eight loads are in flight at a time
     float s = 0.f;

@@ -68,7 +68,8 @@ __global__ __launch_bounds__(256) void score_generic_kernel(
   const int s = cand ? cand[qrow * k_cand + slot] : slot;
   float result = -INFINITY;
   if (s >= 0 && s < n) {
-    const char* krow = static_cast<const char*>(K) + ((size_t)seq * p.L + s) * KV::ROW_BYTES;
+    const size_t kslot = key_slot(p, seq, s);
+    const char* krow = static_cast<const char*>(K) + kslot * KV::ROW_BYTES;
     float total = 0.f;
     for (int hg = 0; hg < hpad; hg += 8) {
       float acc[8];
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(256) void score_generic_kernel(
 #pragma unroll
       for (int j = 0; j < 8; ++j) total = fmaf(wsm[hg + j], relu(acc[j]), total);
     }
-    if (KDT == MISA_FP8_E4M3) total *= kscale[(size_t)seq * p.L + s];
+    if (KDT == MISA_FP8_E4M3) total *= kscale[kslot];
     result = total;
   }
   out[qrow * row_len + slot] = result;
@@ -111,7 +112,7 @@ union Frag {
 
 // NT = 16-row head tiles (heads <= 16 * NT); a wavefront takes STEPS pipeline
 // steps of G 64-key groups each.
-template <int KDT, int NT, int STEPS, int G>
+template <int KDT, int NT, int STEPS, int G, bool PAGED>
 __global__ __launch_bounds__(256) void score_stream_kernel(
     Prob p, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
@@ -146,16 +147,33 @@ __global__ __launch_bounds__(256) void score_stream_kernel(
   // Loads are unconditional and branch-free (rows clamped into the cache), so
   // that the number of loads in flight is known at every wait.
   struct Raw { uint4 v[4][NLD]; float scale; };
+  // Page pool: a 64-key group starts at a multiple of 64, so with pages of 64 tokens or more
+  // all its keys (and the last key, when rows are clamped to it) lie in one page, found with
+  // one wavefront-uniform table read; smaller pages are looked up per lane.
   auto issue_loads = [&](Raw& r, int kg) {
+    size_t group_slot = 0;
+    const bool one_page = PAGED && p.page_shift >= 6;
+    if (one_page)
+      group_slot = (size_t)p.page_table[(size_t)seq * p.max_pages + (min(kg, p.L - 1) >> p.page_shift)] << p.page_shift;
+    const int in_page = (1 << p.page_shift) - 1;
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt) {
       const int row = min(kg + tt * 16 + c, p.L - 1);
-      const uint4* src = reinterpret_cast<const uint4*>(kbase + (size_t)row * ROW_BYTES) + g;
+      const uint4* src;
+      if (!PAGED) src = reinterpret_cast<const uint4*>(kbase + (size_t)row * ROW_BYTES) + g;
+      else {
+        const size_t slot = one_page ? group_slot + (row & in_page) : key_slot<true>(p, seq, row);
+        src = reinterpret_cast<const uint4*>(static_cast<const char*>(K) + slot * ROW_BYTES) + g;
+      }
 #pragma unroll
       for (int i = 0; i < NLD; ++i) r.v[tt][i] = src[4 * i];
     }
     r.scale = 1.f;
-    if (KDT == MISA_FP8_E4M3) r.scale = sbase[min(kg + lane, p.L - 1)];
+    if (KDT == MISA_FP8_E4M3) {
+      const int row = min(kg + lane, p.L - 1);
+      if (!PAGED) r.scale = sbase[row];
+      else r.scale = kscale[one_page ? group_slot + (row & in_page) : key_slot<true>(p, seq, row)];
+    }
   };
 
   auto finish_group = [&](const Raw& r, int kg) {
@@ -314,7 +332,7 @@ constexpr int kStageCap = 256;  // filter mode: staged candidates per wavefront 
 //   with the half) and moves them to the global lists in batches, one global
 //   atomic per query and batch.
 // The work of one workgroup: query tile q_tile of sequence blockIdx.z, key range blockIdx.x.
-template <int KDT, int HS, int MODE>
+template <int KDT, int HS, int MODE, bool PAGED>
 __device__ __forceinline__ void score_tile_body(
     const Prob& p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
@@ -383,7 +401,7 @@ __device__ __forceinline__ void score_tile_body(
     }
   }
 
-  const char* kbase = static_cast<const char*>(K) + (size_t)seq * p.L * ROW_BYTES;
+  const char* kbase = static_cast<const char*>(K) + (PAGED ? (size_t)0 : (size_t)seq * p.L * ROW_BYTES);
   // Staging registers of the next key tile (global -> registers -> LDS).  Thread
   // tid moves the 16-byte chunks tid + 256 i of the tile.
   constexpr int CPR = ROW_BYTES / 16;  // chunks per key row
@@ -391,10 +409,11 @@ __device__ __forceinline__ void score_tile_body(
   float st_scale = 1.f;
   // Cache row of key j of tile space (clamped into the cache).  Sampling takes key
   // 16 j + (top four bits of a multiplicative hash of j) of every group of 16.
+  // With a page table the row is the one in the page pool and kbase the pool itself.
   auto key_row = [&](int j) -> size_t {
     j = min(j, LT - 1);
-    if (SAMPLE) return (size_t)j * kSampleStride + (((uint32_t)j * 2654435761u) >> 28);
-    return (size_t)j;
+    if (SAMPLE) j = j * kSampleStride + (int)(((uint32_t)j * 2654435761u) >> 28);
+    return PAGED ? key_slot<true>(p, seq, j) : (size_t)j;
   };
 #define MISA_TILE_LOAD(k0)                                                                        \
   do {                                                                                            \
@@ -404,7 +423,7 @@ __device__ __forceinline__ void score_tile_body(
       st2 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 512) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
       st3 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 768) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
     }                                                                                             \
-    if (KDT == MISA_FP8_E4M3 && tid < kKT) st_scale = kscale[(size_t)seq * p.L + key_row((k0) + tid)]; \
+    if (KDT == MISA_FP8_E4M3 && tid < kKT) st_scale = kscale[(PAGED ? (size_t)0 : (size_t)seq * p.L) + key_row((k0) + tid)]; \
   } while (0)
   auto put_chunk = [&](int b, int chunk, const uint4& v) {  // registers -> LDS, bf16, padded rows
     const int row = chunk / CPR, c = chunk % CPR;
@@ -672,25 +691,25 @@ __device__ __forceinline__ void score_tile_body(
 
 // Two wavefronts per SIMD (at most 256 vector registers) except for 64 head slots, whose
 // four row tiles need the whole register file.
-template <int KDT, int HS, int MODE>
+template <int KDT, int HS, int MODE, bool PAGED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HS == 64 ? 1 : 2, HS == 64 ? 1 : 2)))
 void score_tile_kernel(
     Prob p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
     float* __restrict__ S, TileAux aux) {
-  score_tile_body<KDT, HS, MODE>(p, keys_per_wg, Q, W, heads, K, kscale, S, aux, blockIdx.y);
+  score_tile_body<KDT, HS, MODE, PAGED>(p, keys_per_wg, Q, W, heads, K, kscale, S, aux, blockIdx.y);
 }
 
 // Store mode for the flagged query tiles only (aux.run).  Normally none is
 // flagged, so the grid is kept small: blockIdx.y strides over the query tiles.
-template <int KDT, int HS>
+template <int KDT, int HS, bool PAGED>
 __global__ __launch_bounds__(256) void score_tile_repair_kernel(
     Prob p, int keys_per_wg, int q_tiles, const uint16_t* __restrict__ Q,
     const float* __restrict__ W, const int* __restrict__ heads, const void* __restrict__ K,
     const float* __restrict__ kscale, float* __restrict__ S, TileAux aux) {
   for (int qt = blockIdx.y; qt < q_tiles; qt += gridDim.y) {
     if (!aux.run[blockIdx.z * q_tiles + qt]) continue;
-    score_tile_body<KDT, HS, kTileStore>(p, keys_per_wg, Q, W, heads, K, kscale, S, aux, qt);
+    score_tile_body<KDT, HS, kTileStore, PAGED>(p, keys_per_wg, Q, W, heads, K, kscale, S, aux, qt);
     __syncthreads();
   }
 }
@@ -721,7 +740,6 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
   const int c_end = min(c_begin + kGatherChunk, k_cand);
   const int* crow = cand + qrow * k_cand;
   float* orow = out + qrow * k_cand;
-  const char* kbase = static_cast<const char*>(K) + (size_t)seq * p.L * ROW_BYTES;
 
   // The candidate indices of this workgroup go through LDS, so that reading them
   // in the loop does not wait on the key loads in flight.
@@ -757,11 +775,12 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
     if (slot >= c_end || s >= n) s = -1;
     r.s = s;
     const int row = max(s, 0);
-    const uint4* src = reinterpret_cast<const uint4*>(kbase + (size_t)row * ROW_BYTES + hf * (ROW_BYTES / 2));
+    const size_t kslot = key_slot(p, seq, row);
+    const uint4* src = reinterpret_cast<const uint4*>(static_cast<const char*>(K) + kslot * ROW_BYTES + hf * (ROW_BYTES / 2));
 #pragma unroll
     for (int i = 0; i < NLD; ++i) r.v[i] = src[i];
     r.scale = 1.f;
-    if (KDT == MISA_FP8_E4M3) r.scale = kscale[(size_t)seq * p.L + row];
+    if (KDT == MISA_FP8_E4M3) r.scale = kscale[kslot];
   };
   auto finish = [&](const Raw& r, int c0) {
     if (c0 >= c_end) return;
@@ -842,7 +861,10 @@ static hipError_t launch_stream(const Prob& p, const void* Q, const float* W, co
   do {                                                                                            \
     constexpr int KPW = 256 * (STEPS);                                                            \
     const dim3 grid((p.L + KPW - 1) / KPW, p.n_q, p.n_seq);                                       \
-    score_stream_kernel<KDT, NT, STEPS, 1><<<grid, 256, 0, st>>>(p, q, W, heads, K, kscale, S);   \
+    if (p.page_table)                                                                             \
+      score_stream_kernel<KDT, NT, STEPS, 1, true><<<grid, 256, 0, st>>>(p, q, W, heads, K, kscale, S);  \
+    else                                                                                          \
+      score_stream_kernel<KDT, NT, STEPS, 1, false><<<grid, 256, 0, st>>>(p, q, W, heads, K, kscale, S); \
   } while (0)
   switch (nt) {
     case 1:
@@ -881,7 +903,11 @@ static hipError_t launch_tile(const Prob& p, const void* Q, const float* W, cons
   if (MODE == kTileStore && aux.run) {
     // about one resident set of workgroups, each striding over the query tiles
     grid.y = (unsigned)std::max(1, std::min(q_tiles, (int)(512 / ((long long)grid.x * p.n_seq))));
-#define GO(HS) score_tile_repair_kernel<KDT, HS><<<grid, 256, 0, st>>>(p, keys_per_wg, q_tiles, q, W, heads, K, kscale, S, aux)
+#define GO(HS)                                                                                                      \
+  if (p.page_table)                                                                                                 \
+    score_tile_repair_kernel<KDT, HS, true><<<grid, 256, 0, st>>>(p, keys_per_wg, q_tiles, q, W, heads, K, kscale, S, aux); \
+  else                                                                                                              \
+    score_tile_repair_kernel<KDT, HS, false><<<grid, 256, 0, st>>>(p, keys_per_wg, q_tiles, q, W, heads, K, kscale, S, aux)
     switch (hs) {
       case 8: GO(8); break;
       case 16: GO(16); break;
@@ -891,7 +917,11 @@ static hipError_t launch_tile(const Prob& p, const void* Q, const float* W, cons
 #undef GO
     return hipGetLastError();
   }
-#define GO(HS) score_tile_kernel<KDT, HS, MODE><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S, aux)
+#define GO(HS)                                                                                               \
+  if (p.page_table)                                                                                          \
+    score_tile_kernel<KDT, HS, MODE, true><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S, aux); \
+  else                                                                                                       \
+    score_tile_kernel<KDT, HS, MODE, false><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S, aux)
   switch (hs) {
     case 8: GO(8); break;
     case 16: GO(16); break;

@@ -32,7 +32,8 @@ class misa_problem(ctypes.Structure):
     _fields_ = [("n_seq", ctypes.c_int32), ("L", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("n_q", ctypes.c_int32), ("H", ctypes.c_int32), ("B", ctypes.c_int32),
                 ("h", ctypes.c_int32), ("k_dtype", ctypes.c_int32), ("q_dtype", ctypes.c_int32),
-                ("q_pos", ctypes.c_void_p), ("seq_len", ctypes.c_void_p)]
+                ("q_pos", ctypes.c_void_p), ("seq_len", ctypes.c_void_p),
+                ("page_table", ctypes.c_void_p), ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32)]
 
 
 _P = ctypes.POINTER(misa_problem)
@@ -114,19 +115,27 @@ class Problem:
     q_pos: Optional[torch.Tensor] = None     # int32 device [n_q] or None (decode)
     seq_len: Optional[torch.Tensor] = None   # int32 device [n_seq] or None
     d: int = 128
+    page_table: Optional[torch.Tensor] = None  # int32 device [n_seq, max_pages] or None (contiguous keys)
+    page_size: int = 0
 
     @property
     def M(self) -> int:
         return -(-self.L // self.B)
 
     def c(self) -> misa_problem:
-        for t in (self.q_pos, self.seq_len):
+        for t in (self.q_pos, self.seq_len, self.page_table):
             if t is not None and (t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous()):
-                raise ValueError("q_pos / seq_len must be contiguous int32 device tensors")
+                raise ValueError("q_pos / seq_len / page_table must be contiguous int32 device tensors")
+        pt = self.page_table
+        if pt is not None and (pt.dim() != 2 or pt.shape[0] != self.n_seq):
+            raise ValueError("page_table must have shape [n_seq, max_pages]")
         return misa_problem(self.n_seq, self.L, self.d, self.n_q, self.H, self.B, self.h,
                             self.k_dtype, self.q_dtype,
                             self.q_pos.data_ptr() if self.q_pos is not None else None,
-                            self.seq_len.data_ptr() if self.seq_len is not None else None)
+                            self.seq_len.data_ptr() if self.seq_len is not None else None,
+                            pt.data_ptr() if pt is not None else None,
+                            self.page_size if pt is not None else 0,
+                            pt.shape[1] if pt is not None else 0)
 
 
 def version() -> int:
@@ -274,6 +283,41 @@ def to_device(inp: dict, device="cuda") -> dict:
     }
     out["problem"] = Problem(wl.n_seq, wl.L, wl.n_q, wl.H, wl.B, wl.h, DTYPE_CODES[wl.k_dtype],
                              DTYPE_CODES[wl.q_dtype], out["q_pos"], out["seq_len"])
+    return out
+
+
+def paginate(dv: dict, page_size: int, seed: int = 0, spare_pages: int = 3) -> dict:
+    """The same inputs with the key cache laid out as a page pool.
+
+    Every sequence's keys are cut into pages of page_size tokens that are scattered over a pool
+    [n_pages, page_size, d] by a seeded permutation (a few pages of the pool stay unused); pool
+    rows that hold no key are filled with a bit pattern no key has.  Returns a copy of dv with K /
+    kscale replaced by the pools and problem.page_table / page_size set.
+    """
+    from dataclasses import replace
+    p = dv["problem"]
+    K, ks = dv["K"], dv["kscale"]
+    per_seq = -(-p.L // page_size)
+    n_pages = p.n_seq * per_seq + spare_pages
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    table = torch.randperm(n_pages, generator=g)[: p.n_seq * per_seq].to(torch.int32).view(p.n_seq, per_seq)
+    table = table.to(K.device)
+    pad = per_seq * page_size - p.L
+    fill = {torch.uint8: 0x7E, torch.bfloat16: 1.0e30, torch.float32: 1.0e30}[K.dtype]
+
+    def pool_of(x, fillv):
+        tail = x.shape[2:]
+        padded = torch.full((p.n_seq, per_seq * page_size) + tail, fillv, dtype=x.dtype, device=x.device)
+        padded[:, : p.L] = x
+        pool = torch.full((n_pages, page_size) + tail, fillv, dtype=x.dtype, device=x.device)
+        pool[table.view(-1).long()] = padded.view((p.n_seq * per_seq, page_size) + tail)
+        return pool.contiguous()
+
+    out = dict(dv)
+    out["K"] = pool_of(K, fill)
+    out["kscale"] = None if ks is None else pool_of(ks, 1.0e30)
+    out["problem"] = replace(p, page_table=table.contiguous(), page_size=page_size)
     return out
 
 

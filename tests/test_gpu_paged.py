@@ -1,0 +1,125 @@
+"""Paged key cache: every call must return, bit for bit, what it returns for the same keys
+stored contiguously (the contiguous path is the one compared with the oracle elsewhere),
+whatever the page size and however the pages are scattered over the pool."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from paper_2605_07363_amd import workloads as WL
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def misa():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2605_07363_amd import misa as m
+    return m
+
+
+def small(name, **kw):
+    return WL.scaled(WL.WORKLOADS[name], **kw)
+
+
+CASES = {
+    "f32_decode": small("c0", L=1500, B=64),
+    "bf16_decode": small("c1", n_seq=3, L=5000, B=64, k=300),
+    "fp8_decode": small("c3", n_seq=2, L=4133, B=128, k=300, needles=16),
+    "fp8_decode_batch": small("c3", n_seq=9, L=3000, B=8, k=100, needles=8),
+    "bf16_prefill": small("c2", L=4500, n_q=70, B=64, k=200),
+    "fp8_prefill": small("c4", L=4200, n_q=40, B=64, k=128, k_cand=512, needles=16),
+    "bf16_prefill_h16": small("c2", L=1500, n_q=21, h=16, B=64, k=100),
+    "fp8_B1024": small("c3", n_seq=2, L=7000, B=3000, k=200, needles=8),
+}
+
+
+def both(misa, name, page_size, ragged=False):
+    wl = CASES[name]
+    seq_len = None
+    if ragged:
+        rng = np.random.default_rng(7)
+        seq_len = rng.integers(1, wl.L + 1, wl.n_seq).astype(np.int32)
+        seq_len[0] = wl.L
+    inp = WL.make_inputs(wl, seed=99 + sum(map(ord, name)), seq_len=seq_len)
+    dv = misa.to_device(inp)
+    return wl, dv, misa.paginate(dv, page_size, seed=page_size)
+
+
+def run_stages(misa, wl, dv):
+    """Every stage once, each on the outputs of the one before; returns all results."""
+    p = dv["problem"]
+    K, ks, Q, W = dv["K"], dv["kscale"], dv["Q"], dv["W"]
+    out = {}
+    Kp = torch.empty((wl.n_seq, p.M, wl.d), dtype=torch.float32, device="cuda")
+    misa.pool_keys(p, K, ks, Kp, misa.alloc_workspace(p, misa.OP_POOL))
+    out["Kp"] = Kp
+    heads = torch.empty((wl.n_seq, wl.n_q, wl.h), dtype=torch.int32, device="cuda")
+    E = torch.empty((wl.n_seq, wl.n_q, wl.H), dtype=torch.float32, device="cuda")
+    misa.route_heads(p, Q, W, Kp, K, ks, heads, E, misa.alloc_workspace(p, misa.OP_ROUTE))
+    out["heads"], out["E"] = heads, E
+    S = torch.empty((wl.n_seq, wl.n_q, wl.L), dtype=torch.float32, device="cuda")
+    misa.score_tokens(p, Q, W, heads, K, ks, S)
+    out["S"] = S
+    D = torch.empty_like(S)
+    misa.score_tokens(p, Q, W, None, K, ks, D)          # dense: all heads
+    out["S_dense"] = D
+    k1 = min(wl.k_cand or wl.k, wl.L)
+    idx = torch.empty((wl.n_seq, wl.n_q, k1), dtype=torch.int32, device="cuda")
+    misa.topk(p, S, k1, idx, None, misa.alloc_workspace(p, misa.OP_TOPK, k1))
+    out["idx"] = idx
+    k2 = min(wl.k, k1)
+    fin = torch.empty((wl.n_seq, wl.n_q, k2), dtype=torch.int32, device="cuda")
+    val = torch.empty((wl.n_seq, wl.n_q, k2), dtype=torch.float32, device="cuda")
+    misa.rerank(p, Q, W, K, ks, idx, k1, k2, fin, val, misa.alloc_workspace(p, misa.OP_RERANK, k1))
+    out["rerank_idx"], out["rerank_val"] = fin, val
+    return out
+
+
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("page_size", [16, 64, 256])
+def test_every_stage_matches_the_contiguous_layout(misa, name, page_size):
+    wl, dv, pg = both(misa, name, page_size, ragged=(page_size == 64))
+    a = run_stages(misa, wl, dv)
+    b = run_stages(misa, wl, pg)
+    for key in a:
+        assert torch.equal(a[key], b[key]), f"{key} differs between the layouts ({name}, pages of {page_size})"
+
+
+def test_pool_update_select_and_comparison_indexers(misa):
+    # the remaining entry points on a prefill problem large enough for the fused call
+    wl = small("c2", L=8192, n_q=256, B=128, k=256)
+    dv = misa.to_device(WL.make_inputs(wl, seed=5))
+    pg = misa.paginate(dv, 128, seed=1)
+    res = []
+    for d in (dv, pg):
+        p = d["problem"]
+        K, ks, Q, W = d["K"], d["kscale"], d["Q"], d["W"]
+        ix = misa.Indexer(p, wl.k, fused=True)
+        sel = ix.run(K, ks, Q, W).clone()
+        # pooled keys maintained from token 5000 on
+        Kp = ix.Kp.clone()
+        Kp[:, 5000 // wl.B:] = 7.0
+        start = torch.full((wl.n_seq,), 5000, dtype=torch.int32, device="cuda")
+        misa.pool_keys_update(p, K, ks, Kp, start, p.M, misa.alloc_workspace(p, misa.OP_POOL))
+        assert torch.equal(Kp, ix.Kp)
+        m = 8
+        hidx = torch.empty((wl.n_seq, wl.n_q, wl.k), dtype=torch.int32, device="cuda")
+        misa.hisa_select(p, Q, W, ix.Kp, K, ks, m, wl.k, hidx, None, None, misa.alloc_workspace(p, misa.OP_HISA, m))
+        res.append((sel, hidx))
+    assert torch.equal(res[0][0], res[1][0])
+    assert torch.equal(res[0][1], res[1][1])
+
+
+def test_page_table_validation(misa):
+    wl = CASES["bf16_decode"]
+    dv = misa.to_device(WL.make_inputs(wl, seed=1))
+    pg = misa.paginate(dv, 64)
+    p = pg["problem"]
+    Kp = torch.empty((wl.n_seq, p.M, wl.d), dtype=torch.float32, device="cuda")
+    for bad in (replace(p, page_size=48), replace(p, page_size=8),
+                replace(p, page_table=p.page_table[:, :5].contiguous())):
+        with pytest.raises(misa.MisaError):
+            misa.pool_keys(bad, pg["K"], pg["kscale"], Kp)

@@ -90,3 +90,29 @@ def test_binding_refuses_host_tensors(misa):
     p = _prob(misa)
     with pytest.raises(ValueError):
         misa.pool_keys(p, torch.zeros(4), None, torch.zeros(4))
+
+
+def test_page_table_and_probe_arguments(misa):
+    INVALID = 1
+    base = _prob(misa).c()
+
+    def paged(**kw):
+        c = _prob(misa).c()
+        c.page_table, c.page_size, c.max_pages = 0x2000, 64, 16          # 16 pages of 64 cover L = 1000
+        for k, v in kw.items():
+            setattr(c, k, v)
+        return misa.lib.misa_pool_keys(ctypes.byref(c), FAKE, None, FAKE, None, 0, None)
+
+    for kw in (dict(page_size=48), dict(page_size=8), dict(page_size=1 << 17), dict(max_pages=15),
+               dict(page_table=None)):                                    # sizes without a table
+        assert paged(**kw) == INVALID, kw
+    assert b"page" in misa.lib.misa_last_error()
+    assert base.page_table is None and base.page_size == 0 and base.max_pages == 0
+    # probes: argument checks come before any launch
+    assert misa.lib.misa_probe_hbm_read(None, 8192, FAKE, None) == INVALID
+    assert misa.lib.misa_probe_hbm_read(FAKE, 8192, None, None) == INVALID
+    assert misa.lib.misa_probe_hbm_read(FAKE, 1000, FAKE, None) == INVALID          # not a multiple of 8192
+    assert misa.lib.misa_probe_hbm_read(ctypes.c_void_p(0x1004), 8192, FAKE, None) == INVALID
+    assert misa.lib.misa_probe_mfma_bf16(0, 1, FAKE, None, None) == INVALID
+    assert misa.lib.misa_probe_mfma_bf16(1, 0, FAKE, None, None) == INVALID
+    assert misa.lib.misa_probe_mfma_bf16(1, 1, None, None, None) == INVALID

@@ -88,6 +88,9 @@ def main() -> int:
                          "the block of the newest token (misa_pool_keys_update), as a serving loop would")
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_SIZE",
                     help="keep the key cache as a pool of scattered pages of PAGE_SIZE tokens (misa_problem.page_table)")
+    ap.add_argument("--fp8-queries", action="store_true",
+                    help="queries stored as e4m3 codes (scale folded into the gates); a step then starts with "
+                         "misa_convert_queries and the stages run on the widened queries")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate", type=int, default=3, help="key-cache copies rotated between steps (cold reads)")
     ap.add_argument("--no-graph", action="store_true",
@@ -105,7 +108,8 @@ def main() -> int:
     from paper_2605_07363_amd import misa, workloads as WL
 
     wl = WL.WORKLOADS[args.workload]
-    override = {k: v for k, v in (("B", args.block), ("h", args.active_heads)) if v}
+    override = {k: v for k, v in (("B", args.block), ("h", args.active_heads),
+                                  ("q_dtype", "e4m3" if args.fp8_queries else None)) if v}
     if override:
         wl = WL.scaled(wl, **override)
     torch.cuda.set_device(0)
@@ -116,6 +120,12 @@ def main() -> int:
         dv = misa.paginate(dv, args.paged, seed=1)
     p = dv["problem"]
     Q, W = dv["Q"], dv["W"]
+    Q8, p8 = None, None
+    if args.fp8_queries:
+        from dataclasses import replace as _replace
+        Q8, p8 = Q, p
+        Q = torch.empty(Q8.shape, dtype=torch.bfloat16, device="cuda")
+        p = _replace(p, q_dtype=misa.BF16)
     # Decode caches are far larger than the 256 MB last-level cache; rotating
     # copies keeps every step's key reads cold.  Prefill caches are small and
     # are re-read by every query tile, so one copy is the workload.
@@ -135,14 +145,15 @@ def main() -> int:
         for r in range(n_rot):                       # all copies hold the same keys: pool once
             ix.pool(Ks[r], scales[r])
 
-    stage_names = ["pool", "route"] + (["select"] if args.fused else ["score", "topk"]) + \
-        (["rerank"] if wl.k_cand else [])
+    stage_names = (["widen"] if args.fp8_queries else []) + ["pool", "route"] + \
+        (["select"] if args.fused else ["score", "topk"]) + (["rerank"] if wl.k_cand else [])
 
     def step(i, ev=None):
         K, ks = Ks[i % n_rot], scales[i % n_rot]
         mid = [lambda: ix.select_fused(Q, W, K, ks)] if args.fused else [lambda: ix.score(Q, W, K, ks), ix.select]
         pool = (lambda: ix.pool_update(K, ks, newest, 1)) if args.incremental_pool else (lambda: ix.pool(K, ks))
-        calls = [pool, lambda: ix.route(Q, W, K, ks)] + mid + \
+        calls = ([lambda: misa.convert_queries(p8, Q8, Q)] if args.fp8_queries else []) + \
+            [pool, lambda: ix.route(Q, W, K, ks)] + mid + \
             ([lambda: ix.refine(Q, W, K, ks)] if wl.k_cand else [])
         for j, c in enumerate(calls):
             if ev is not None:

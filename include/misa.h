@@ -20,6 +20,7 @@
  *                             routing-score ablation
  *   misa_hisa_select,         the HISA and Block-Sparse comparison indexers
  *   misa_block_sparse_select
+ *   misa_convert_queries      fp8 query codes -> bf16 (fp8 queries are accepted by every call)
  *   misa_probe_hbm_read,      achievable read and matrix rates of the machine,
  *   misa_probe_mfma_bf16      for roofline reports
  *
@@ -107,7 +108,7 @@ typedef struct misa_problem {
   int32_t B;              /* router block size, >= 1 (any value, also >= L)           */
   int32_t h;              /* active heads, 1..H                                       */
   int32_t k_dtype;        /* misa_dtype of K                                          */
-  int32_t q_dtype;        /* misa_dtype of Q (F32 or BF16)                            */
+  int32_t q_dtype;        /* misa_dtype of Q (see "fp8 queries" below for FP8_E4M3)    */
   const int32_t* q_pos;   /* device [n_q], shared by all sequences; NULL = decode:
                              every query sits at the last position (n = len_i)       */
   const int32_t* seq_len; /* device [n_seq] or NULL (every sequence holds L keys)     */
@@ -301,6 +302,21 @@ misa_status misa_hisa_select(const misa_problem* p, const void* Q, const float* 
 misa_status misa_block_sparse_select(const misa_problem* p, const void* Q, const float* W,
                                      const float* Kp, int32_t m, int32_t* blocks, int32_t* idx,
                                      void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * fp8 queries (q_dtype = MISA_FP8_E4M3; the paper notes that DSA quantises its indexer to
+ * FP8): Q is [n_seq, n_q, H, d] uint8 e4m3 codes WITHOUT a scale array.  A positive
+ * per-(query, head) scale c belongs into the gate: w ReLU((c q) . k) = (c w) ReLU(q . k), so
+ * the caller passes W[i,t,j] * c[i,t,j].  Every e4m3 value is also a bf16 value: each call that
+ * takes Q widens the codes to bf16 at the head of its workspace (misa_workspace_bytes
+ * includes that room; misa_route_heads_proxy reads the codes directly) and proceeds exactly
+ * as for bf16 queries, so results equal those of the widened queries bit for bit.  A caller
+ * that runs several stages on the same queries widens them once with misa_convert_queries
+ * and passes the result with q_dtype = MISA_BF16.
+ *   Q       in   [n_seq, n_q, H, d] uint8, 16-byte aligned (p->q_dtype must be MISA_FP8_E4M3)
+ *   Q_bf16  out  [n_seq, n_q, H, d] bf16, 16-byte aligned
+ */
+misa_status misa_convert_queries(const misa_problem* p, const void* Q, void* Q_bf16, void* stream);
 
 /*
  * Measurement probes (not part of the method; for callers that report rates against

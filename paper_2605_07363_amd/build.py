@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmisa.so")
-SOURCES = ["api.hip", "pool.hip", "route.hip", "score.hip", "topk.hip", "select.hip", "hisa.hip", "peaks.hip"]
+SOURCES = ["api.hip", "pool.hip", "route.hip", "score.hip", "topk.hip", "select.hip", "hisa.hip", "peaks.hip", "convert.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

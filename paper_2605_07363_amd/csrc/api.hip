@@ -37,7 +37,6 @@ misa_status check_problem(const misa_problem* p, misa::Prob* out) {
     return fail(MISA_ERR_INVALID_ARG, "q_pos is required when n_q > 1");
   if (p->d != misa::kD) return fail(MISA_ERR_UNSUPPORTED, "d must be 128 (got %d)", p->d);
   if (p->H > misa::kMaxH) return fail(MISA_ERR_UNSUPPORTED, "H must be <= 64 (got %d)", p->H);
-  if (p->q_dtype == MISA_FP8_E4M3) return fail(MISA_ERR_UNSUPPORTED, "fp8 queries are not supported");
   if (p->L > misa::kMaxRowLen) return fail(MISA_ERR_UNSUPPORTED, "L must be <= 524288 (got %d)", p->L);
   if (p->n_seq > 65535 || p->n_q > 65535)
     return fail(MISA_ERR_UNSUPPORTED, "n_seq and n_q must be <= 65535");
@@ -90,6 +89,34 @@ misa_status hip_result(hipError_t e, const char* what) {
   return fail(MISA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+// fp8 query codes are widened to bf16 (exact) at the head of the workspace; the kernels then
+// see bf16 queries and the rest of the workspace.
+struct QView { const void* Q; int q_dtype; void* ws; size_t ws_bytes; };
+
+size_t q_stage_bytes(const misa_problem* p) {
+  if (p->q_dtype != MISA_FP8_E4M3) return 0;
+  const size_t b = (size_t)p->n_seq * p->n_q * p->H * misa::kD * 2;
+  return (b + 255) & ~(size_t)255;
+}
+
+int eff_q_dtype(const misa_problem* p) { return p->q_dtype == MISA_FP8_E4M3 ? MISA_BF16 : p->q_dtype; }
+
+misa_status stage_queries(const misa_problem* p, const void* Q, size_t need_rest, void* ws,
+                          size_t ws_bytes, void* stream, QView* v) {
+  const size_t qb = q_stage_bytes(p);
+  misa_status st = check_ws(need_rest + qb, ws, ws_bytes);
+  if (st != MISA_OK) return st;
+  v->Q = Q; v->q_dtype = p->q_dtype; v->ws = ws; v->ws_bytes = ws_bytes;
+  if (qb) {
+    hipError_t e = misa::launch_widen_queries(Q, ws, (size_t)p->n_seq * p->n_q * p->H * misa::kD,
+                                              (hipStream_t)stream);
+    if (e != hipSuccess) return hip_result(e, "query widening launch");
+    v->Q = ws; v->q_dtype = MISA_BF16;
+    v->ws = static_cast<char*>(ws) + qb; v->ws_bytes = ws_bytes - qb;
+  }
+  return MISA_OK;
+}
+
 size_t ws_bytes_for(const misa::Prob& pr, int op, int k, int k_dtype = 0, int q_dtype = 0) {
   switch (op) {
     case MISA_OP_SELECT: return misa::select_ws_bytes(pr, k_dtype, q_dtype, k);
@@ -115,7 +142,9 @@ size_t misa_workspace_bytes(const misa_problem* p, int32_t op, int32_t k) {
   misa::Prob pr;
   if (check_problem(p, &pr) != MISA_OK) return 0;
   if (op < MISA_OP_POOL || op > MISA_OP_HISA) return 0;
-  return ws_bytes_for(pr, op, k, p->k_dtype, p->q_dtype);
+  const bool takes_queries = op == MISA_OP_ROUTE || op == MISA_OP_SCORE || op == MISA_OP_RERANK ||
+                             op == MISA_OP_SELECT || op == MISA_OP_HISA;
+  return ws_bytes_for(pr, op, k, p->k_dtype, eff_q_dtype(p)) + (takes_queries ? q_stage_bytes(p) : 0);
 }
 
 misa_status misa_pool_keys(const misa_problem* p, const void* K, const float* kscale, float* Kp,
@@ -154,8 +183,9 @@ misa_status misa_route_heads(const misa_problem* p, const void* Q, const float* 
   if ((st = check_queries(Q, W)) != MISA_OK) return st;
   if ((st = check_keys(p, K, kscale)) != MISA_OK) return st;
   if (!Kp || !heads) return fail(MISA_ERR_INVALID_ARG, "Kp or heads is NULL");
-  if ((st = check_ws(ws_bytes_for(pr, MISA_OP_ROUTE, 0), ws, ws_bytes)) != MISA_OK) return st;
-  return hip_result(misa::launch_route(pr, p->k_dtype, p->q_dtype, Q, W, Kp, K, kscale, heads, E, ws,
+  QView qv;
+  if ((st = stage_queries(p, Q, ws_bytes_for(pr, MISA_OP_ROUTE, 0), ws, ws_bytes, stream, &qv)) != MISA_OK) return st;
+  return hip_result(misa::launch_route(pr, p->k_dtype, qv.q_dtype, qv.Q, W, Kp, K, kscale, heads, E, qv.ws,
                                        (hipStream_t)stream),
                     "misa_route_heads launch");
 }
@@ -176,14 +206,15 @@ misa_status misa_route_heads_proxy(const misa_problem* p, const void* Q, const f
 misa_status misa_score_tokens(const misa_problem* p, const void* Q, const float* W,
                               const int32_t* heads, const void* K, const float* kscale, float* S,
                               void* ws, size_t ws_bytes, void* stream) {
-  (void)ws; (void)ws_bytes;
   misa::Prob pr;
   misa_status st = check_problem(p, &pr);
   if (st != MISA_OK) return st;
   if ((st = check_queries(Q, W)) != MISA_OK) return st;
   if ((st = check_keys(p, K, kscale)) != MISA_OK) return st;
   if (!S) return fail(MISA_ERR_INVALID_ARG, "S is NULL");
-  return hip_result(misa::launch_score(pr, p->k_dtype, p->q_dtype, Q, W, heads, K, kscale, nullptr, 0,
+  QView qv;
+  if ((st = stage_queries(p, Q, 0, ws, ws_bytes, stream, &qv)) != MISA_OK) return st;
+  return hip_result(misa::launch_score(pr, p->k_dtype, qv.q_dtype, qv.Q, W, heads, K, kscale, nullptr, 0,
                                        S, (hipStream_t)stream),
                     "misa_score_tokens launch");
 }
@@ -212,9 +243,11 @@ misa_status misa_select_tokens(const misa_problem* p, const void* Q, const float
   if (!idx) return fail(MISA_ERR_INVALID_ARG, "idx is NULL");
   if (k < 1) return fail(MISA_ERR_INVALID_ARG, "k must be >= 1 (got %d)", k);
   if (k > misa::kMaxTopK) return fail(MISA_ERR_UNSUPPORTED, "k must be <= 16384 (got %d)", k);
-  if ((st = check_ws(ws_bytes_for(pr, MISA_OP_SELECT, k, p->k_dtype, p->q_dtype), ws, ws_bytes)) != MISA_OK)
+  QView qv;
+  if ((st = stage_queries(p, Q, ws_bytes_for(pr, MISA_OP_SELECT, k, p->k_dtype, eff_q_dtype(p)), ws, ws_bytes,
+                          stream, &qv)) != MISA_OK)
     return st;
-  return hip_result(misa::launch_select(pr, p->k_dtype, p->q_dtype, Q, W, heads, K, kscale, k, idx, val,
+  return hip_result(misa::launch_select(pr, p->k_dtype, qv.q_dtype, qv.Q, W, heads, K, kscale, k, idx, val,
                                         ws, (hipStream_t)stream),
                     "misa_select_tokens launch");
 }
@@ -222,7 +255,8 @@ misa_status misa_select_tokens(const misa_problem* p, const void* Q, const float
 int64_t misa_select_row_flags_offset(const misa_problem* p, int32_t routed, int32_t k) {
   misa::Prob pr;
   if (check_problem(p, &pr) != MISA_OK) return -1;
-  return misa::select_row_flags_offset(pr, p->k_dtype, p->q_dtype, routed != 0, k);
+  const long long off = misa::select_row_flags_offset(pr, p->k_dtype, eff_q_dtype(p), routed != 0, k);
+  return off < 0 ? off : off + (long long)q_stage_bytes(p);
 }
 
 namespace {
@@ -246,8 +280,9 @@ misa_status misa_hisa_select(const misa_problem* p, const void* Q, const float* 
   if ((st = check_block_budget(pr, m)) != MISA_OK) return st;
   if (k < 1 || (long long)k > (long long)m * pr.B)
     return fail(MISA_ERR_INVALID_ARG, "need 1 <= k <= m * B (k=%d, m=%d, B=%d)", k, m, pr.B);
-  if ((st = check_ws(ws_bytes_for(pr, MISA_OP_HISA, m), ws, ws_bytes)) != MISA_OK) return st;
-  return hip_result(misa::launch_hisa(pr, p->k_dtype, p->q_dtype, Q, W, Kp, K, kscale, m, k, blocks, idx,
+  QView qv;
+  if ((st = stage_queries(p, Q, ws_bytes_for(pr, MISA_OP_HISA, m), ws, ws_bytes, stream, &qv)) != MISA_OK) return st;
+  return hip_result(misa::launch_hisa(pr, p->k_dtype, qv.q_dtype, qv.Q, W, Kp, K, kscale, m, k, blocks, idx,
                                       val, ws, (hipStream_t)stream),
                     "misa_hisa_select launch");
 }
@@ -261,8 +296,9 @@ misa_status misa_block_sparse_select(const misa_problem* p, const void* Q, const
   if ((st = check_queries(Q, W)) != MISA_OK) return st;
   if (!Kp || !idx) return fail(MISA_ERR_INVALID_ARG, "Kp or idx is NULL");
   if ((st = check_block_budget(pr, m)) != MISA_OK) return st;
-  if ((st = check_ws(ws_bytes_for(pr, MISA_OP_HISA, m), ws, ws_bytes)) != MISA_OK) return st;
-  return hip_result(misa::launch_hisa(pr, p->k_dtype, p->q_dtype, Q, W, Kp, nullptr, nullptr, m, 0, blocks,
+  QView qv;
+  if ((st = stage_queries(p, Q, ws_bytes_for(pr, MISA_OP_HISA, m), ws, ws_bytes, stream, &qv)) != MISA_OK) return st;
+  return hip_result(misa::launch_hisa(pr, p->k_dtype, qv.q_dtype, qv.Q, W, Kp, nullptr, nullptr, m, 0, blocks,
                                       idx, nullptr, ws, (hipStream_t)stream),
                     "misa_block_sparse_select launch");
 }
@@ -280,13 +316,27 @@ misa_status misa_rerank(const misa_problem* p, const void* Q, const float* W, co
     return fail(MISA_ERR_INVALID_ARG, "need 1 <= k <= k_cand (k=%d, k_cand=%d)", k, k_cand);
   if (k_cand > misa::kMaxTopK)
     return fail(MISA_ERR_UNSUPPORTED, "k_cand must be <= 16384 (got %d)", k_cand);
-  if ((st = check_ws(ws_bytes_for(pr, MISA_OP_RERANK, k_cand), ws, ws_bytes)) != MISA_OK) return st;
-  float* dense = static_cast<float*>(ws);
-  hipError_t e = misa::launch_score(pr, p->k_dtype, p->q_dtype, Q, W, nullptr, K, kscale, cand, k_cand,
+  QView qv;
+  if ((st = stage_queries(p, Q, ws_bytes_for(pr, MISA_OP_RERANK, k_cand), ws, ws_bytes, stream, &qv)) != MISA_OK) return st;
+  float* dense = static_cast<float*>(qv.ws);
+  hipError_t e = misa::launch_score(pr, p->k_dtype, qv.q_dtype, qv.Q, W, nullptr, K, kscale, cand, k_cand,
                                     dense, (hipStream_t)stream);
   if (e != hipSuccess) return hip_result(e, "misa_rerank score launch");
   return hip_result(misa::launch_topk(pr, dense, k_cand, k, cand, idx, val, nullptr, (hipStream_t)stream),
                     "misa_rerank top-k launch");
+}
+
+misa_status misa_convert_queries(const misa_problem* p, const void* Q, void* Q_bf16, void* stream) {
+  misa::Prob pr;
+  misa_status st = check_problem(p, &pr);
+  if (st != MISA_OK) return st;
+  if (p->q_dtype != MISA_FP8_E4M3) return fail(MISA_ERR_INVALID_ARG, "q_dtype must be MISA_FP8_E4M3");
+  if (!Q || !Q_bf16) return fail(MISA_ERR_INVALID_ARG, "Q or Q_bf16 is NULL");
+  if (!aligned(Q, 16) || !aligned(Q_bf16, 16))
+    return fail(MISA_ERR_INVALID_ARG, "Q and Q_bf16 must be 16-byte aligned");
+  return hip_result(misa::launch_widen_queries(Q, Q_bf16, (size_t)p->n_seq * p->n_q * p->H * misa::kD,
+                                               (hipStream_t)stream),
+                    "misa_convert_queries launch");
 }
 
 misa_status misa_probe_hbm_read(const void* buf, size_t bytes, void* sink, void* stream) {

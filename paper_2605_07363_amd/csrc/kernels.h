@@ -2,6 +2,8 @@
 // launches; arguments were validated by the C ABI layer before.
 #pragma once
 
+#include <algorithm>
+
 #include "common.h"
 
 namespace misa {
@@ -70,6 +72,9 @@ size_t hisa_ws_bytes(const Prob& p, int m);
 hipError_t launch_hisa(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,
                        const float* Kp, const void* K, const float* kscale, int m, int k, int* blocks,
                        int* idx, float* val, void* ws, hipStream_t st);
+
+// fp8 query codes -> bf16 (convert.hip); n_elems a multiple of 128.
+hipError_t launch_widen_queries(const void* q8, void* q16, size_t n_elems, hipStream_t st);
 
 // Probes for the roofline report (peaks.hip).
 constexpr int kProbeMfmaFlopsPerWaveIter = 4 * 2 * 32 * 32 * 16;

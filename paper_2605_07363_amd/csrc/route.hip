@@ -490,7 +490,8 @@ hipError_t launch_route_proxy(const Prob& p, int q_dtype, int kind, const void* 
                               int* heads, float* E, hipStream_t st) {
   const dim3 grid(p.n_q, p.n_seq);
   if (q_dtype == MISA_F32) route_proxy_kernel<MISA_F32><<<grid, 64, 0, st>>>(p, kind, Q, W, heads, E);
-  else route_proxy_kernel<MISA_BF16><<<grid, 64, 0, st>>>(p, kind, Q, W, heads, E);
+  else if (q_dtype == MISA_BF16) route_proxy_kernel<MISA_BF16><<<grid, 64, 0, st>>>(p, kind, Q, W, heads, E);
+  else route_proxy_kernel<MISA_FP8_E4M3><<<grid, 64, 0, st>>>(p, kind, Q, W, heads, E);
   return hipGetLastError();
 }
 

@@ -63,6 +63,8 @@ lib.misa_hisa_select.argtypes = [_P, _V, _V, _V, _V, _V, ctypes.c_int32, ctypes.
                                  ctypes.c_size_t, _V]
 lib.misa_block_sparse_select.restype = ctypes.c_int
 lib.misa_block_sparse_select.argtypes = [_P, _V, _V, _V, ctypes.c_int32, _V, _V, _V, ctypes.c_size_t, _V]
+lib.misa_convert_queries.restype = ctypes.c_int
+lib.misa_convert_queries.argtypes = [_P, _V, _V, _V]
 lib.misa_probe_hbm_read.restype = ctypes.c_int
 lib.misa_probe_hbm_read.argtypes = [_V, ctypes.c_size_t, _V, _V]
 lib.misa_probe_mfma_bf16.restype = ctypes.c_int
@@ -221,6 +223,11 @@ def block_sparse_select(p: Problem, Q, W, Kp, m: int, idx, blocks=None, ws=None)
                                         _ptr(idx), w, wb, _stream()))
 
 
+def convert_queries(p: Problem, Q, Q_bf16) -> None:
+    """fp8 (e4m3) query codes -> bf16 values (exact); p.q_dtype must be FP8_E4M3."""
+    _check(lib.misa_convert_queries(ctypes.byref(p.c()), _ptr(Q), _ptr(Q_bf16), _stream()))
+
+
 def probe_hbm_read(buf, sink, nbytes: Optional[int] = None) -> int:
     """Enqueues one read of the first nbytes bytes of buf (default: all, rounded down to 8 KiB); returns nbytes."""
     total = buf.numel() * buf.element_size()
@@ -372,7 +379,15 @@ class Indexer:
                self.ws[OP_RERANK])
 
     def run(self, K, kscale, Q, W, pool=True):
-        """One pass of the whole indexer; returns the selected token indices."""
+        """One pass of the whole indexer; returns the selected token indices.  fp8 queries are
+        widened to bf16 once here instead of inside each of the stage calls."""
+        if self.p.q_dtype == FP8_E4M3:
+            from dataclasses import replace
+            if getattr(self, "_q16", None) is None:
+                self._q16 = torch.empty(Q.shape, dtype=torch.bfloat16, device=Q.device)
+                self._p8, self.p = self.p, replace(self.p, q_dtype=BF16)
+            convert_queries(self._p8, Q, self._q16)
+            Q = self._q16
         if pool:
             self.pool(K, kscale)
         self.route(Q, W, K, kscale)

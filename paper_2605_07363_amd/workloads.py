@@ -33,7 +33,7 @@ class Workload:
     k: int            # final token budget
     k_cand: int       # MISA-dagger candidate budget k' (0 = single stage)
     k_dtype: str      # 'f32' | 'bf16' | 'e4m3'
-    q_dtype: str      # 'f32' | 'bf16'
+    q_dtype: str      # 'f32' | 'bf16' | 'e4m3' (codes; the per-(query, head) scale is folded into W)
     decode: bool      # True: one query at the last position, q_pos = None
     structure: str    # 'iid' | 'topic'
     needles: int      # planted needle keys per sequence
@@ -114,8 +114,14 @@ def _store(x: np.ndarray, dtype: str):
 
 
 def stored_to_f32(x: np.ndarray, dtype: str) -> np.ndarray:
-    """Stored queries -> the float32 values they represent (used to build needles)."""
-    return x if dtype == "f32" else bf16_bits_to_f32(x)
+    """Stored queries -> the float32 values they represent (used to build needles; fp8 codes
+    without their scale, which does not change a direction)."""
+    if dtype == "f32":
+        return x
+    if dtype == "e4m3":
+        import torch
+        return torch.from_numpy(np.ascontiguousarray(x)).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    return bf16_bits_to_f32(x)
 
 
 # ---------------------------------------------------------------------------
@@ -156,7 +162,11 @@ def make_inputs(wl: Workload, seed: int | None = None, seq_len=None) -> dict:
             home = np.arange(H) % TOPICS
             match = (home[None, :] == q_topic[:, None])             # [nq, H]
             q += (np.float32(TOPIC_QUERY_AMPL) * match[:, :, None]) * topics[q_topic][:, None, :]
-        q_st, _ = _store(q, wl.q_dtype)
+        q_st, q_sc = _store(q, wl.q_dtype)
+        if wl.q_dtype == "e4m3":
+            # fp8 queries carry no scale array: w ReLU((c q).k) = (c w) ReLU(q.k) for c > 0, so the
+            # per-(query, head) scale goes into the gate (this product is input data for both sides)
+            w = (w * q_sc).astype(np.float32)
         q_val = stored_to_f32(q_st, wl.q_dtype)
 
         # keys

@@ -12,7 +12,9 @@ def oracle_view(inp, seq, t):
     """(K float64 [L,d], q [H,d], w [H], n) of one query as the oracle sees it."""
     wl = inp["wl"]
     K = O.dequantise(inp["K"][seq], wl.k_dtype, None if inp["kscale"] is None else inp["kscale"][seq])
-    q = O.dequantise(inp["Q"][seq, t], wl.q_dtype)
+    qs = inp["Q"][seq, t]
+    # fp8 query codes carry no scale (it is folded into W by the generator)
+    q = O.dequantise(qs, wl.q_dtype, np.ones(qs.shape[:-1], np.float32) if wl.q_dtype == "e4m3" else None)
     w = inp["W"][seq, t].astype(np.float64)
     length = wl.L if inp["seq_len"] is None else int(np.clip(inp["seq_len"][seq], 0, wl.L))
     n = length if inp["q_pos"] is None else int(np.clip(int(inp["q_pos"][t]) + 1, 0, length))

@@ -20,7 +20,7 @@ def test_every_declared_symbol_is_exported(misa):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(misa_[a-z0-9_]+)\s*\(", header))
     assert {"misa_pool_keys", "misa_route_heads", "misa_score_tokens", "misa_topk", "misa_rerank", "misa_select_tokens", "misa_hisa_select", "misa_block_sparse_select", "misa_pool_keys_update", "misa_route_heads_proxy",
-            "misa_probe_hbm_read", "misa_probe_mfma_bf16",
+            "misa_probe_hbm_read", "misa_probe_mfma_bf16", "misa_convert_queries",
             "misa_workspace_bytes", "misa_last_error", "misa_version"} <= names
     for n in names:
         assert hasattr(misa.lib, n), f"{n} declared in misa.h but not exported"
@@ -46,7 +46,7 @@ def test_invalid_problem_fields_are_rejected_without_launch(misa):
                dict(k_dtype=7), dict(q_dtype=-1), dict(n_q=2)):   # n_q > 1 without q_pos
         assert _pool(misa, _prob(misa, **kw)) == INVALID, kw
         assert misa.lib.misa_last_error() != b""
-    for kw in (dict(d=64), dict(H=128, h=8), dict(q_dtype=misa.FP8_E4M3), dict(L=1 << 20),
+    for kw in (dict(d=64), dict(H=128, h=8), dict(L=1 << 20),
                dict(n_seq=70000)):
         assert _pool(misa, _prob(misa, **kw)) == UNSUPPORTED, kw
     assert misa.lib.misa_pool_keys(None, FAKE, None, FAKE, None, 0, None) == INVALID

@@ -20,8 +20,9 @@
 // that a few thousand elements pass, at least k of them but for a negligible
 // chance) and hands the elements of its key range that pass to topk_kernel<true>,
 // which selects exactly among them.  A row whose hand-over is not usable (fewer
-// than k passed, or too many for the list) is redone by the same workgroup
-// with the two passes over the row, so the result never depends on the sample.
+// than k passed, too many for the list, or too many tied around the k-th) is
+// redone by the same workgroup with the two passes over the row, so the result
+// never depends on the sample.
 #include "kernels.h"
 #include "radix.h"
 

@@ -31,6 +31,21 @@ __device__ __forceinline__ void load_query_head(const void* Q, size_t head_index
   for (int c = 0; c < kD / V::N; ++c) V::load(src + c * 16, qv + c * V::N);
 }
 
+// Two fp32 values -> two packed bf16 pairs whose sums represent them to 2^-17 relative: hi is
+// the bf16 nearest to the value, lo the bf16 nearest to the (exactly computed) remainder.
+// Element 0 sits in the low half of each word.
+typedef __bf16 bf16x2_r __attribute__((ext_vector_type(2)));
+typedef float f32x2_r __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void split_pair(float x0, float x1, uint32_t& hi, uint32_t& lo) {
+  union { bf16x2_r b; uint32_t u; } h, l;
+  const f32x2_r v = {x0, x1};
+  h.b = __builtin_convertvector(v, bf16x2_r);
+  const f32x2_r r = {x0 - __uint_as_float(h.u << 16), x1 - __uint_as_float(h.u & 0xFFFF0000u)};
+  l.b = __builtin_convertvector(r, bf16x2_r);
+  hi = h.u;
+  lo = l.u;
+}
+
 // Blocks whose pooled key in Kp is valid for a query with prefix n: all
 // ceil(n/B) when the query sits at the end of the cache (the partial block in
 // Kp then holds exactly its tokens), else only the complete ones.
@@ -165,17 +180,13 @@ __global__ __launch_bounds__(256) void route_tile_kernel(Prob p, int splits,
       const int e = tid + 256 * i;
       const int row = e >> 5, c4 = e & 31;        // c4: group of 4 components
       const float x[4] = {stage[i].x, stage[i].y, stage[i].z, stage[i].w};
-      uint32_t hi[4], lo[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t u = __float_as_uint(x[j]);
-        hi[j] = u & 0xFFFF0000u;                                   // upper 16 bits: exact bf16
-        lo[j] = __float_as_uint(x[j] - __uint_as_float(hi[j])) & 0xFFFF0000u;
-      }
+      uint32_t hi[2], lo[2];
+      split_pair(x[0], x[1], hi[0], lo[0]);
+      split_pair(x[2], x[3], hi[1], lo[1]);
       // 16-byte chunk c4 / 2 of the row, XOR-swizzled by the row; 8-byte half c4 & 1
       const int slot = row * 32 + (((c4 >> 1) ^ (row & 15)) << 1) + (c4 & 1);
-      tile[buf][0][slot] = make_uint2((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
-      tile[buf][1][slot] = make_uint2((lo[0] >> 16) | lo[1], (lo[2] >> 16) | lo[3]);
+      tile[buf][0][slot] = make_uint2(hi[0], hi[1]);
+      tile[buf][1][slot] = make_uint2(lo[0], lo[1]);
     }
   };
 
@@ -313,16 +324,12 @@ __global__ __launch_bounds__(256) void route_wave_kernel(Prob p, int tiles_per_w
     for (int ks = 0; ks < 8; ++ks) {
       const float v[8] = {x[ks][0].x, x[ks][0].y, x[ks][0].z, x[ks][0].w,
                           x[ks][1].x, x[ks][1].y, x[ks][1].z, x[ks][1].w};
-      uint32_t hi[8], lo[8];
+      uint32_t hi[4], lo[4];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const uint32_t u = __float_as_uint(v[j]);
-        hi[j] = u & 0xFFFF0000u;                                   // upper 16 bits: exact bf16
-        lo[j] = __float_as_uint(v[j] - __uint_as_float(hi[j])) & 0xFFFF0000u;
-      }
+      for (int j = 0; j < 4; ++j) split_pair(v[2 * j], v[2 * j + 1], hi[j], lo[j]);
       RFrag bh, bl;
-      bh.u = make_uint4((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3], (hi[4] >> 16) | hi[5], (hi[6] >> 16) | hi[7]);
-      bl.u = make_uint4((lo[0] >> 16) | lo[1], (lo[2] >> 16) | lo[3], (lo[4] >> 16) | lo[5], (lo[6] >> 16) | lo[7]);
+      bh.u = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+      bl.u = make_uint4(lo[0], lo[1], lo[2], lo[3]);
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, bh.v, acc[rt], 0, 0, 0);

@@ -24,8 +24,10 @@ def misa():
     return m
 
 
-def run_and_check(misa, wl, inp, rows=None):
+def run_and_check(misa, wl, inp, rows=None, page_size=0):
     dv = misa.to_device(inp)
+    if page_size:
+        dv = misa.paginate(dv, page_size, seed=page_size)
     ix = misa.Indexer(dv["problem"], wl.k, wl.k_cand, want_E=True, want_val=True)
     ix.run(dv["K"], dv["kscale"], dv["Q"], dv["W"])
     torch.cuda.synchronize()

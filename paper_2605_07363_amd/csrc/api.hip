@@ -248,7 +248,7 @@ misa_status misa_select_tokens(const misa_problem* p, const void* Q, const float
                           stream, &qv)) != MISA_OK)
     return st;
   return hip_result(misa::launch_select(pr, p->k_dtype, qv.q_dtype, qv.Q, W, heads, K, kscale, k, idx, val,
-                                        ws, (hipStream_t)stream),
+                                        qv.ws, (hipStream_t)stream),
                     "misa_select_tokens launch");
 }
 
@@ -283,7 +283,7 @@ misa_status misa_hisa_select(const misa_problem* p, const void* Q, const float* 
   QView qv;
   if ((st = stage_queries(p, Q, ws_bytes_for(pr, MISA_OP_HISA, m), ws, ws_bytes, stream, &qv)) != MISA_OK) return st;
   return hip_result(misa::launch_hisa(pr, p->k_dtype, qv.q_dtype, qv.Q, W, Kp, K, kscale, m, k, blocks, idx,
-                                      val, ws, (hipStream_t)stream),
+                                      val, qv.ws, (hipStream_t)stream),
                     "misa_hisa_select launch");
 }
 
@@ -299,7 +299,7 @@ misa_status misa_block_sparse_select(const misa_problem* p, const void* Q, const
   QView qv;
   if ((st = stage_queries(p, Q, ws_bytes_for(pr, MISA_OP_HISA, m), ws, ws_bytes, stream, &qv)) != MISA_OK) return st;
   return hip_result(misa::launch_hisa(pr, p->k_dtype, qv.q_dtype, qv.Q, W, Kp, nullptr, nullptr, m, 0, blocks,
-                                      idx, nullptr, ws, (hipStream_t)stream),
+                                      idx, nullptr, qv.ws, (hipStream_t)stream),
                     "misa_block_sparse_select launch");
 }
 

@@ -38,6 +38,25 @@ CASES = {
 }
 
 
+def _random_case(i):
+    rng = np.random.default_rng(7000 + i)
+    decode = bool(rng.integers(0, 2))
+    H = int(rng.choice([1, 8, 17, 32, 64]))
+    L = int(rng.integers(60, 4000))
+    B = int(rng.choice([1, 5, 16, 64, 128, 700]))
+    m = int(rng.integers(2, max(3, min(16384 // B, 40))))
+    k = int(rng.integers(1, min(m * B, 400) + 1))
+    wl = WL.scaled(WL.WORKLOADS["c3" if decode else "c2"], n_seq=int(rng.integers(1, 4)), L=L,
+                   n_q=1 if decode else int(rng.integers(2, 40)), H=H, h=int(rng.integers(1, H + 1)), B=B, k=k,
+                   k_cand=0, k_dtype=["f32", "bf16", "e4m3"][i % 3], q_dtype=["bf16", "e4m3", "f32"][(i // 3) % 3],
+                   needles=int(rng.integers(0, 9)), name=f"random{i}")
+    return wl, m
+
+
+RANDOM = {f"random{i}": _random_case(i) for i in range(18)}
+CASES.update(RANDOM)
+
+
 def forced_scores(J):
     J = J.copy()
     if J.shape[0]:
@@ -46,12 +65,14 @@ def forced_scores(J):
     return J
 
 
-def run(misa, name, seq_len=None, q_pos=None):
+def run(misa, name, seq_len=None, q_pos=None, page_size=0):
     wl, m = CASES[name]
     inp = WL.make_inputs(wl, seed=300 + sum(map(ord, name)), seq_len=seq_len)
     if q_pos is not None:
         inp["q_pos"] = np.asarray(q_pos, dtype=np.int32)
     dv = misa.to_device(inp)
+    if page_size:
+        dv = misa.paginate(dv, page_size, seed=3)
     p = dv["problem"]
     rows = (wl.n_seq, wl.n_q)
     Kp = torch.empty((wl.n_seq, p.M, wl.d), dtype=torch.float32, device="cuda")
@@ -102,11 +123,23 @@ def check(inp, wl, m, blocks, idx, val, bs_idx):
     return exact
 
 
-@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("name", [n for n in CASES if n not in RANDOM])
 def test_hisa_and_block_sparse_match_oracle(misa, name):
     inp, wl, m, blocks, idx, val, bs_idx = run(misa, name)
     exact = check(inp, wl, m, blocks, idx, val, bs_idx)
     assert exact >= 0.9 * wl.n_seq * wl.n_q
+
+
+@pytest.mark.parametrize("name", list(RANDOM))
+def test_hisa_random_problems(misa, name):
+    # seeded random shapes, storage types, ragged batches, unsorted query positions, paged keys
+    wl, m = CASES[name]
+    rng = np.random.default_rng(sum(map(ord, name)))
+    seq_len = rng.integers(0, wl.L + 1, wl.n_seq).astype(np.int32) if rng.integers(0, 2) else None
+    q_pos = rng.integers(0, wl.L, wl.n_q) if (not wl.decode and rng.integers(0, 2)) else None
+    inp, wl, m, blocks, idx, val, bs_idx = run(misa, name, seq_len=seq_len, q_pos=q_pos,
+                                               page_size=int(rng.choice([0, 16, 128])))
+    check(inp, wl, m, blocks, idx, val, bs_idx)
 
 
 def test_hisa_with_all_blocks_is_the_dense_indexer(misa):

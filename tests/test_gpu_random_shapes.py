@@ -93,3 +93,16 @@ def test_random_problem_fused_call_equals_two_calls(misa, seed):
     ib = b.run(dv["K"], dv["kscale"], dv["Q"], dv["W"])
     assert torch.equal(ia, ib)
     assert torch.equal(a.val, b.val)
+    if wl.q_dtype == "e4m3":
+        # stage by stage on the codes themselves: every call widens them inside its own workspace
+        c = misa.Indexer(p, wl.k, want_val=True, fused=True)
+        c.pool(dv["K"], dv["kscale"])
+        c.route(dv["Q"], dv["W"], dv["K"], dv["kscale"])
+        c.select_fused(dv["Q"], dv["W"], dv["K"], dv["kscale"])
+        assert torch.equal(c.idx, ia) and torch.equal(c.val, a.val)
+        d = misa.Indexer(p, wl.k, want_val=True)
+        d.pool(dv["K"], dv["kscale"])
+        d.route(dv["Q"], dv["W"], dv["K"], dv["kscale"])
+        d.score(dv["Q"], dv["W"], dv["K"], dv["kscale"])
+        d.select()
+        assert torch.equal(d.idx, ia) and torch.equal(d.S, a.S)

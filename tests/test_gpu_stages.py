@@ -455,3 +455,104 @@ def test_measurement_probes_report_plausible_rates(misa):
     # operands are 1.0 x {0.5, 1.0}: every accumulator element is 3 iterations x 16 products
     got = sink.cpu().numpy()
     assert set(np.unique(got).tolist()) <= {4 * 16 * 3 * 16 * 0.5, 4 * 16 * 3 * 16 * 1.0, 4 * 16 * 3 * 16 * 0.75}
+
+
+# --------------------------------------------------------------------- random top-k rows
+@pytest.mark.parametrize("seed", range(30))
+def test_topk_random_distributions(misa, seed):
+    # shapes on both sides of every path switch (one workgroup per row / key ranges per row; sampled
+    # hand-over usable or not), value distributions with heavy tails, plateaus, ties and -inf
+    rng = np.random.default_rng(9000 + seed)
+    L = int(rng.choice([int(rng.integers(1, 3000)), int(rng.integers(3000, 40000)), int(rng.integers(32768, 150000))]))
+    n_seq = int(rng.integers(1, 4))
+    n_q = 1 if rng.integers(0, 2) else int(rng.integers(2, 6))
+    k = int(min(rng.choice([1, 7, 100, 1000, 2048, 5000, 9000, 16384]), 16384))
+    kind = seed % 6
+    shape = (n_seq, n_q, L)
+    if kind == 0:
+        S = rng.standard_normal(shape)
+    elif kind == 1:
+        S = rng.standard_cauchy(shape)                                   # heavy tails both ways
+    elif kind == 2:
+        S = np.round(rng.standard_normal(shape) * 4) / 4                 # many exact ties
+    elif kind == 3:
+        S = np.maximum(rng.standard_normal(shape), 0.0)                  # half the row exactly zero (ReLU scores)
+    elif kind == 4:
+        S = rng.standard_normal(shape)
+        S[..., : L // 3] += 50.0                                         # a plateau far above the rest
+    else:
+        S = np.exp(rng.standard_normal(shape) * 3)
+        S[rng.random(shape) < 0.3] = -np.inf
+    S = S.astype(np.float32)
+    q_pos = None if n_q == 1 else rng.integers(0, L, n_q).astype(np.int32)
+    seq_len = rng.integers(0, L + 1, n_seq).astype(np.int32) if rng.integers(0, 2) else None
+    _topk_case(misa, S, k, q_pos=q_pos, seq_len=seq_len)
+
+
+# --------------------------------------------------------------------- random re-rank / pooled-key updates
+@pytest.mark.parametrize("seed", range(12))
+def test_rerank_random_candidate_lists(misa, seed):
+    rng = np.random.default_rng(9500 + seed)
+    decode = bool(rng.integers(0, 2))
+    H = int(rng.choice([1, 8, 17, 32, 64]))
+    L = int(rng.integers(30, 3000))
+    wl = WL.scaled(WL.WORKLOADS["c3" if decode else "c2"], n_seq=int(rng.integers(1, 4)), L=L,
+                   n_q=1 if decode else int(rng.integers(2, 30)), H=H, h=1, B=64, k=1, k_cand=0,
+                   k_dtype=["f32", "bf16", "e4m3"][seed % 3], q_dtype=["bf16", "e4m3", "f32"][(seed // 3) % 3],
+                   needles=4, name=f"rr{seed}")
+    inp = WL.make_inputs(wl, seed=seed, seq_len=rng.integers(0, L + 1, wl.n_seq).astype(np.int32) if seed % 2 else None)
+    dv = misa.to_device(inp)
+    if seed % 4 == 3:
+        dv = misa.paginate(dv, 32, seed=seed)
+    p = dv["problem"]
+    kc = int(rng.integers(1, min(L, 2500) + 1))
+    k = int(rng.integers(1, kc + 1))
+    cand = np.full((wl.n_seq, wl.n_q, kc), -1, dtype=np.int32)
+    for s in range(wl.n_seq):
+        for t in range(wl.n_q):
+            c = np.sort(rng.choice(L, size=int(rng.integers(0, kc + 1)), replace=False)).astype(np.int32)
+            c[rng.random(c.shape[0]) < 0.05] = -1                 # holes
+            cand[s, t, :c.shape[0]] = c
+    idx = torch.empty((wl.n_seq, wl.n_q, k), dtype=torch.int32, device="cuda")
+    val = torch.empty((wl.n_seq, wl.n_q, k), dtype=torch.float32, device="cuda")
+    misa.rerank(p, dv["Q"], dv["W"], dv["K"], dv["kscale"], torch.from_numpy(cand).cuda(), kc, k, idx, val,
+                misa.alloc_workspace(p, misa.OP_RERANK, kc))
+    idx, val = idx.cpu().numpy(), val.cpu().numpy()
+    for s in range(wl.n_seq):
+        for t in range(wl.n_q):
+            K, q, w, n = oracle_view(inp, s, t)
+            dense = O.dsa_scores(q, w, K, n) if n else np.zeros(0)
+            valid = np.array(sorted(c for c in cand[s, t] if 0 <= c < n), dtype=np.int64)
+            ke = min(k, valid.shape[0])
+            got = idx[s, t]
+            assert np.all(got[ke:] == -1) and np.all(np.diff(got[:ke]) > 0)
+            assert set(got[:ke].tolist()) <= set(valid.tolist())
+            pos = np.searchsorted(valid, got[:ke])
+            padded = np.concatenate([pos, np.full(k - ke, -1, dtype=pos.dtype)])
+            check_index_set(padded, dense[valid], k, f"rerank rr{seed} {s},{t}")
+            assert_scores_close(val[s, t, :ke], dense[got[:ke]], f"rerank values rr{seed} {s},{t}")
+            assert np.all(np.isneginf(val[s, t, ke:]))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_pool_update_random(misa, seed):
+    from dataclasses import replace
+    rng = np.random.default_rng(9700 + seed)
+    L = int(rng.integers(10, 9000))
+    B = int(rng.choice([1, 3, 64, 128, 1024, 2500, L + 1]))
+    wl = WL.scaled(WL.WORKLOADS["c3"], n_seq=int(rng.integers(1, 5)), L=L, B=B, k=1, needles=0,
+                   k_dtype=["f32", "bf16", "e4m3"][seed % 3], name=f"pu{seed}")
+    new_len = rng.integers(0, L + 1, wl.n_seq).astype(np.int32)
+    old_len = (new_len - rng.integers(0, 3 * B + 2, wl.n_seq)).clip(0).astype(np.int32)
+    dv = misa.to_device(WL.make_inputs(wl, seed=seed, seq_len=new_len))
+    if seed % 3 == 1:
+        dv = misa.paginate(dv, 64, seed=seed)
+    p_new = dv["problem"]
+    ws = misa.alloc_workspace(p_new, misa.OP_POOL)
+    full = torch.full((wl.n_seq, p_new.M, wl.d), 7.0, dtype=torch.float32, device="cuda")
+    misa.pool_keys(p_new, dv["K"], dv["kscale"], full, ws)
+    old_dev = torch.from_numpy(old_len).cuda()
+    Kp = torch.full_like(full, 7.0)
+    misa.pool_keys(replace(p_new, seq_len=old_dev), dv["K"], dv["kscale"], Kp, ws)
+    misa.pool_keys_update(p_new, dv["K"], dv["kscale"], Kp, old_dev, p_new.M, ws)
+    assert torch.equal(Kp, full)

@@ -115,3 +115,15 @@ def _sample_rows(wl, count, seed=3):
 def test_full_size_sampled_rows(misa, name, count):
     wl = WL.WORKLOADS[name]
     run_and_check(misa, wl, WL.make_inputs(wl), _sample_rows(wl, count))
+
+
+@pytest.mark.parametrize("name,kw,rows,page", [
+    ("c1", dict(n_seq=2, L=524288, k=2048), [(1, 0)], 0),
+    ("c3", dict(n_seq=1, L=524288, k=16384, B=1024), [(0, 0)], 256),
+    ("c4", dict(L=524288, n_q=64, k=2048, k_cand=16384, B=128), [(0, 0), (0, 63)], 0),
+])
+def test_longest_supported_prefix(misa, name, kw, rows, page):
+    # L = 524288 (the documented limit), k and k' up to 16384, contiguous and paged
+    wl = WL.scaled(WL.WORKLOADS[name], **kw)
+    st = run_and_check(misa, wl, WL.make_inputs(wl, seed=4), rows=rows, page_size=page)
+    assert st["rows"] == len(rows)

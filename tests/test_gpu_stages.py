@@ -556,3 +556,25 @@ def test_pool_update_random(misa, seed):
     misa.pool_keys(replace(p_new, seq_len=old_dev), dv["K"], dv["kscale"], Kp, ws)
     misa.pool_keys_update(p_new, dv["K"], dv["kscale"], Kp, old_dev, p_new.M, ws)
     assert torch.equal(Kp, full)
+
+
+@pytest.mark.parametrize("seed", range(9))
+def test_route_heads_proxy_random(misa, seed):
+    rng = np.random.default_rng(9900 + seed)
+    H = int(rng.choice([1, 2, 17, 32, 64]))
+    wl = WL.scaled(WL.WORKLOADS["c2"], n_seq=int(rng.integers(1, 4)), L=64, n_q=int(rng.integers(1, 50)), H=H,
+                   h=int(rng.integers(1, H + 1)), B=16, k=1, needles=0, q_dtype=["bf16", "e4m3", "f32"][seed % 3],
+                   k_dtype="bf16", name=f"proxy{seed}")
+    inp = WL.make_inputs(wl, seed=seed)
+    dv = misa.to_device(inp)
+    for kind, code in (("gate", misa.ROUTER_GATE), ("qnorm", misa.ROUTER_QUERY_NORM)):
+        heads = torch.full((wl.n_seq, wl.n_q, wl.h), -5, dtype=torch.int32, device="cuda")
+        E = torch.empty((wl.n_seq, wl.n_q, wl.H), dtype=torch.float32, device="cuda")
+        misa.route_heads_proxy(dv["problem"], dv["Q"], dv["W"], code, heads, E)
+        heads, E = heads.cpu().numpy(), E.cpu().numpy()
+        for s in range(wl.n_seq):
+            for t in range(wl.n_q):
+                _, q, w, _ = oracle_view(inp, s, t)
+                _, ref_E = O.route_heads_proxy(q, w, wl.h, kind)
+                assert_scores_close(E[s, t], ref_E, f"proxy E {kind} {s},{t}")
+                check_index_set(heads[s, t], ref_E, wl.h, f"proxy heads {kind} {s},{t}")

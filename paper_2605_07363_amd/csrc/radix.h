@@ -15,9 +15,10 @@ constexpr int kBins = 2048;
 // 2047 - i * 2048 / NT downwards.  Writes {d, need - count(digit > d), hist[d]} to out
 // (nothing if need exceeds the total).  Uses scan_scratch[16..31] (block_exclusive_scan uses
 // the lower half); two barriers, the second at the end.
+// need2 > 0: the digit for a second count is searched in the same scan and written to out2.
 template <int NT>
 __device__ __forceinline__ void find_threshold_bin_n(const int* hist, int need, int* scan_scratch,
-                                                     int* out) {
+                                                     int* out, int need2 = 0, int* out2 = nullptr) {
   constexpr int BPT = kBins / NT, NW = NT / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int top = kBins - 1 - BPT * (int)threadIdx.x;
@@ -35,14 +36,17 @@ __device__ __forceinline__ void find_threshold_bin_n(const int* hist, int need, 
     if (above < need && need <= above + h[i]) {
       out[0] = top - i; out[1] = need - above; out[2] = h[i];
     }
+    if (need2 > 0 && above < need2 && need2 <= above + h[i]) {
+      out2[0] = top - i; out2[1] = need2 - above; out2[2] = h[i];
+    }
     above += h[i];
   }
   __syncthreads();
 }
 
 __device__ __forceinline__ void find_threshold_bin(const int* hist, int need, int* scan_scratch,
-                                                   int* out) {
-  find_threshold_bin_n<kTopkThreads>(hist, need, scan_scratch, out);
+                                                   int* out, int need2 = 0, int* out2 = nullptr) {
+  find_threshold_bin_n<kTopkThreads>(hist, need, scan_scratch, out, need2, out2);
 }
 
 template <int NT>

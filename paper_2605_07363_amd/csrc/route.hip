@@ -367,6 +367,7 @@ __global__ __launch_bounds__(128) void route_finalize_kernel(
   __shared__ float tailk[kD];
   __shared__ float Es[kMaxH];
   __shared__ int sel[kMaxH];
+  __shared__ float sred[4][kMaxH];
   using KV = Vec16<KDT>;
   const int t = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
   const int n = visible(p, seq, t), len = seq_length(p, seq);
@@ -396,20 +397,30 @@ __global__ __launch_bounds__(128) void route_finalize_kernel(
     }
     tailk[tid] = s / (float)r;
   }
+  // Partial sums of the block tiles: the 128 threads form 4 (H <= 32) or 2 groups of one thread
+  // per head; group g adds the slots g, g + G, ... in order, eight loads in flight at a time,
+  // and the groups' sums are added in group order below.
+  {
+    const int hp = p.H <= 32 ? 32 : 64, G = 128 / hp, g = tid / hp, j = tid % hp;
+    float s = 0.f;
+    if (j < p.H) {
+      const float* ps = part + ((size_t)seq * p.n_q + t) * splits * kWave + j;
+      for (int sp = g; sp < splits; sp += 8 * G) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = sp + u * G < splits ? ps[(size_t)(sp + u * G) * kWave] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+      }
+    }
+    sred[g][j] = s;
+  }
   __syncthreads();
 
   if (tid < p.H) {
     const size_t qi = ((size_t)seq * p.n_q + t) * p.H + tid;
-    // partial sums are added in slot order; eight loads are in flight at a time
-    float s = 0.f;
-    const float* ps = part + ((size_t)seq * p.n_q + t) * splits * kWave + tid;
-    for (int sp = 0; sp < splits; sp += 8) {
-      float v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = sp + u < splits ? ps[(size_t)(sp + u) * kWave] : 0.f;
-#pragma unroll
-      for (int u = 0; u < 8; ++u) s += v[u];
-    }
+    float s = sred[0][tid] + sred[1][tid];
+    if (p.H <= 32) s += sred[2][tid] + sred[3][tid];
     if (tail) {
       float qv[kD];
       load_query_head<QDT>(Q, qi, qv);

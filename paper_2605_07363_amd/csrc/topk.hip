@@ -78,6 +78,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_prefilter_kernel(Prob p,
   __shared__ int hist2[kBins];
   __shared__ int scan_scratch[32];
   __shared__ int thr[3];
+  __shared__ int thr_up[3];
   __shared__ int cnt;
   constexpr int SPT = kSampleLines * 16 / kTopkThreads;  // samples per thread
   constexpr int U = 8;
@@ -131,18 +132,16 @@ __global__ __launch_bounds__(kTopkThreads) void topk_prefilter_kernel(Prob p,
   uint32_t tau = 0;                    // r > m: everything passes
   uint32_t upper = 0xFFFFFFFFu;        // top of the digit that holds the sample element of rank r/4
   if (r <= m) {
-    find_threshold_bin(hist, r, scan_scratch, thr);
+    find_threshold_bin(hist, r, scan_scratch, thr, max(r / 4, 1), thr_up);
     const uint32_t d1 = thr[0];
     const int need = thr[1];
+    upper = ((uint32_t)thr_up[0] << 21) | 0x1FFFFFu;
 #pragma unroll
     for (int u = 0; u < SPT; ++u)
       if (sin[u] && (skey[u] >> 21) == d1) atomicAdd(&hist2[(skey[u] >> 10) & 0x7FF], 1);
     __syncthreads();
     find_threshold_bin(hist2, need, scan_scratch, thr);
     tau = (d1 << 21) | ((uint32_t)thr[0] << 10);
-    __syncthreads();
-    find_threshold_bin(hist, max(r / 4, 1), scan_scratch, thr);
-    upper = ((uint32_t)thr[0] << 21) | 0x1FFFFFu;
   }
 
   // elements of the range at or above the threshold -> the segment; the count goes on past

@@ -116,3 +116,21 @@ def test_page_table_and_probe_arguments(misa):
     assert misa.lib.misa_probe_mfma_bf16(0, 1, FAKE, None, None) == INVALID
     assert misa.lib.misa_probe_mfma_bf16(1, 0, FAKE, None, None) == INVALID
     assert misa.lib.misa_probe_mfma_bf16(1, 1, None, None, None) == INVALID
+
+
+def test_paginate_places_every_key_where_the_page_table_says(misa):
+    import torch
+    L, P, n_seq = 150, 16, 3
+    K = torch.arange(n_seq * L * 128, dtype=torch.float32).view(n_seq, L, 128)
+    ks = torch.arange(n_seq * L, dtype=torch.float32).view(n_seq, L)
+    p = misa.Problem(n_seq, L, 1, 8, 16, 2, misa.F32, misa.F32)
+    # (the binding only checks devices when a call is made; the layout helper works on any device)
+    pg = misa.paginate({"K": K, "kscale": ks, "problem": p}, P, seed=5)
+    table, pool, spool = pg["problem"].page_table, pg["K"], pg["kscale"]
+    assert table.shape == (n_seq, -(-L // P)) and pg["problem"].page_size == P
+    assert len(set(table.view(-1).tolist())) == table.numel()            # pages are not shared
+    for i in range(n_seq):
+        for s in (0, 1, 15, 16, 17, 100, L - 1):
+            row = int(table[i, s // P]) * P + s % P
+            assert torch.equal(pool.view(-1, 128)[row], K[i, s])
+            assert spool.view(-1)[row] == ks[i, s]

@@ -52,37 +52,26 @@ __global__ __launch_bounds__(256) void pool_kernel(Prob p, int slices, const int
   for (int e = 0; e < N; ++e) acc[e] = 0.f;
 
   const char* base = static_cast<const char*>(K);
-  if (PAGED) {
-    // four rows per round: their page-table entries, then their keys, are in flight together
-    // (rows past the end are clamped and masked; the order of the additions is unchanged)
-    for (long long row0 = lo + r; row0 < hi; row0 += 4 * RPP) {
-      size_t slot[4];
-      float v[4][N], s[4];
+  // four rows per round: their loads (with a page table: their table entries, then their keys)
+  // are in flight together; rows past the end are clamped and masked, the order of the additions
+  // is that of the rows
+  for (long long row0 = lo + r; row0 < hi; row0 += 4 * RPP) {
+    size_t slot[4];
+    float v[4][N], s[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) slot[u] = key_slot<true>(p, seq, (int)min(row0 + u * RPP, hi - 1));
+    for (int u = 0; u < 4; ++u) slot[u] = key_slot<PAGED>(p, seq, (int)min(row0 + u * RPP, hi - 1));
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        V::load(base + slot[u] * V::ROW_BYTES + c * 16, v[u]);
-        s[u] = 1.f;
-        if (DT == MISA_FP8_E4M3) s[u] = kscale[slot[u]];
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (row0 + u * RPP < hi) {
-#pragma unroll
-          for (int e = 0; e < N; ++e) acc[e] = fmaf(v[u][e], s[u], acc[e]);
-        }
-      }
+    for (int u = 0; u < 4; ++u) {
+      V::load(base + slot[u] * V::ROW_BYTES + c * 16, v[u]);
+      s[u] = 1.f;
+      if (DT == MISA_FP8_E4M3) s[u] = kscale[slot[u]];
     }
-  } else {
-    for (long long row = lo + r; row < hi; row += RPP) {
-      float v[N];
-      const size_t slot = key_slot<false>(p, seq, (int)row);
-      V::load(base + slot * V::ROW_BYTES + c * 16, v);
-      float s = 1.f;
-      if (DT == MISA_FP8_E4M3) s = kscale[slot];
 #pragma unroll
-      for (int e = 0; e < N; ++e) acc[e] = fmaf(v[e], s, acc[e]);
+    for (int u = 0; u < 4; ++u) {
+      if (row0 + u * RPP < hi) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) acc[e] = fmaf(v[u][e], s[u], acc[e]);
+      }
     }
   }
 #pragma unroll

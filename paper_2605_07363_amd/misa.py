@@ -383,13 +383,20 @@ class Indexer:
     def run(self, K, kscale, Q, W, pool=True):
         """One pass of the whole indexer; returns the selected token indices.  fp8 queries are
         widened to bf16 once here instead of inside each of the stage calls."""
-        if self.p.q_dtype == FP8_E4M3:
+        if self.p.q_dtype != FP8_E4M3:
+            return self._run(K, kscale, Q, W, pool)
+        if getattr(self, "_q16", None) is None:
             from dataclasses import replace
-            if getattr(self, "_q16", None) is None:
-                self._q16 = torch.empty(Q.shape, dtype=torch.bfloat16, device=Q.device)
-                self._p8, self.p = self.p, replace(self.p, q_dtype=BF16)
-            convert_queries(self._p8, Q, self._q16)
-            Q = self._q16
+            self._q16 = torch.empty(Q.shape, dtype=torch.bfloat16, device=Q.device)
+            self._p16 = replace(self.p, q_dtype=BF16)
+        convert_queries(self.p, Q, self._q16)
+        p8, self.p = self.p, self._p16          # the stage methods below read self.p
+        try:
+            return self._run(K, kscale, self._q16, W, pool)
+        finally:
+            self.p = p8
+
+    def _run(self, K, kscale, Q, W, pool):
         if pool:
             self.pool(K, kscale)
         self.route(Q, W, K, kscale)

@@ -95,7 +95,10 @@ def test_fp8_queries_whole_pipeline_and_fused_call(misa):
     inp = WL.make_inputs(wl, seed=11)
     dv = misa.to_device(inp)
     p = dv["problem"]
-    a = misa.Indexer(p, wl.k).run(dv["K"], dv["kscale"], dv["Q"], dv["W"]).clone()
+    ia = misa.Indexer(p, wl.k)
+    a = ia.run(dv["K"], dv["kscale"], dv["Q"], dv["W"]).clone()
+    ia.idx.fill_(-3)
+    assert torch.equal(ia.run(dv["K"], dv["kscale"], dv["Q"], dv["W"]), a)     # and again on the same object
     b = misa.Indexer(p, wl.k, fused=True).run(dv["K"], dv["kscale"], dv["Q"], dv["W"]).clone()
     assert torch.equal(a, b)
     # the fused call on the codes themselves (widening inside the call)

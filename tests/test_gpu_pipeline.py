@@ -127,3 +127,42 @@ def test_longest_supported_prefix(misa, name, kw, rows, page):
     wl = WL.scaled(WL.WORKLOADS[name], **kw)
     st = run_and_check(misa, wl, WL.make_inputs(wl, seed=4), rows=rows, page_size=page)
     assert st["rows"] == len(rows)
+
+
+@pytest.mark.parametrize("name,kw,fused,page", [
+    ("c3", dict(n_seq=3, L=40000, k=512, needles=16), False, 0),          # decode: top-k over key ranges
+    ("c1", dict(n_seq=2, L=33000, k=300, q_dtype="e4m3"), False, 64),     # fp8 queries widened inside the step, paged keys
+    ("c4", dict(L=9000, n_q=70, k=128, k_cand=512, needles=16), True, 128),  # fused select + re-rank, paged keys
+])
+def test_whole_step_replays_from_a_hip_graph(misa, name, kw, fused, page):
+    # A captured step must reproduce the eager result on every replay, also after the inputs
+    # changed in place and with eager work and synchronisation between the replays.
+    wl = WL.scaled(WL.WORKLOADS[name], **kw)
+    dv = misa.to_device(WL.make_inputs(wl, seed=8))
+    other = misa.to_device(WL.make_inputs(wl, seed=9))
+    if page:
+        dv, other = misa.paginate(dv, page, seed=1), misa.paginate(other, page, seed=1)   # same page table
+    ix = misa.Indexer(dv["problem"], wl.k, wl.k_cand, fused=fused)
+    K, ks, Q, W = dv["K"], dv["kscale"], dv["Q"], dv["W"]
+    expect = {}
+    for tag, src in (("a", dv), ("b", other)):
+        ix.idx.fill_(-7)
+        expect[tag] = ix.run(src["K"], src["kscale"], src["Q"], src["W"]).clone()
+    assert not torch.equal(expect["a"], expect["b"])
+    keep = {n: dv[n].clone() for n in ("K", "Q", "W")}
+    keep_ks = None if ks is None else ks.clone()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        ix.run(K, ks, Q, W)
+    for tag in ("a", "b", "a", "b"):
+        src = {"a": (keep["K"], keep_ks, keep["Q"], keep["W"]),
+               "b": (other["K"], other["kscale"], other["Q"], other["W"])}[tag]
+        K.copy_(src[0]); Q.copy_(src[2]); W.copy_(src[3])                 # eager work between replays
+        if ks is not None:
+            ks.copy_(src[1])
+        ix.idx.fill_(-7)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ix.idx, expect[tag]), tag

@@ -88,14 +88,17 @@ __device__ __forceinline__ int wave_find_bin(const int* hist, int need, int* res
   return __shfl(d, owner);
 }
 
+// upper[row]: the top key of the first radix digit that holds the sampled score of rank r / 4,
+// a robust upper end of the interval in which the k-th largest score lies (select_rows_kernel
+// spreads its first digit over [tau, upper]).
 // One wavefront per row: tau[row] = a value at or just below the r-th largest of the
 // row's visible sampled scores (the lower edge of its 22-bit radix bin, i.e. within
 // 2^-13 relative), so at least r samples reach it.  Also clears the row's candidate
 // count and repair flags.
 __global__ __launch_bounds__(256) void select_threshold_kernel(
     Prob p, const float* __restrict__ Ss, int m, int r, int cap, int qwg, int q_tiles,
-    float* __restrict__ tau, int* __restrict__ count, int* __restrict__ row_flag,
-    int* __restrict__ tile_flag) {
+    float* __restrict__ tau, uint32_t* __restrict__ upper, int* __restrict__ count,
+    int* __restrict__ row_flag, int* __restrict__ tile_flag) {
   __shared__ int hist_all[4][kBins];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = blockIdx.x * 4 + wave;
@@ -109,7 +112,7 @@ __global__ __launch_bounds__(256) void select_threshold_kernel(
     if (t % qwg == 0) tile_flag[seq * q_tiles + t / qwg] = 0;
   }
   if (n <= cap) {  // every visible key fits into the list
-    if (lane == 0) tau[row] = -INFINITY;
+    if (lane == 0) { tau[row] = -INFINITY; upper[row] = 0xFFFFFFFFu; }
     return;
   }
   const int ns = n / kSampleStride;  // visible samples; ns > cap / 16 >= r
@@ -134,6 +137,8 @@ __global__ __launch_bounds__(256) void select_threshold_kernel(
   __builtin_amdgcn_wave_barrier();
   int need;
   const uint32_t d1 = (uint32_t)wave_find_bin(hist, r, &need);
+  int unused;
+  const uint32_t d_up = (uint32_t)wave_find_bin(hist, max(r / 4, 1), &unused);  // a quarter of the way up
   __builtin_amdgcn_wave_barrier();
   for (int i = lane; i < kBins; i += 64) hist[i] = 0;
   __builtin_amdgcn_wave_barrier();
@@ -143,7 +148,10 @@ __global__ __launch_bounds__(256) void select_threshold_kernel(
   __builtin_amdgcn_wave_barrier();
   int rest;
   const uint32_t d2 = (uint32_t)wave_find_bin(hist, need, &rest);
-  if (lane == 0) tau[row] = key_to_float((d1 << 21) | (d2 << 10));
+  if (lane == 0) {
+    tau[row] = key_to_float((d1 << 21) | (d2 << 10));
+    upper[row] = (d_up << 21) | 0x1FFFFFu;
+  }
 }
 
 // ---------------------------------------------------------------- select
@@ -153,13 +161,17 @@ __global__ __launch_bounds__(256) void select_threshold_kernel(
 // several rows share a compute unit.
 template <int NT, int EPT>
 __global__ __launch_bounds__(NT) void select_rows_kernel(
-    Prob p, const int2* __restrict__ cand, const int* __restrict__ count, int cap, int k, int qwg,
+    Prob p, const int2* __restrict__ cand, const int* __restrict__ count,
+    const float* __restrict__ tau, const uint32_t* __restrict__ upper, int cap, int k, int qwg,
     int q_tiles, int* __restrict__ idx, float* __restrict__ val, int* __restrict__ row_flag,
     int* __restrict__ tile_flag) {
   extern __shared__ uint32_t dyn[];  // selection bitmap, then the prefix count of every bitmap word
   __shared__ int hist[kBins];
   __shared__ int scan_scratch[32];
   __shared__ int thr[3];
+  __shared__ uint32_t bkey[64];
+  __shared__ int bidx[64];
+  __shared__ int b_len;
   const int t = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
   const size_t row = (size_t)seq * p.n_q + t;
   const int n = visible(p, seq, t);
@@ -197,14 +209,64 @@ __global__ __launch_bounds__(NT) void select_rows_kernel(
     ek[u] = order_key(ev[u]);
   }
   for (int i = tid; i < nwords; i += NT) sel[i] = 0;
+  if (tid == 0) b_len = 0;
   zero_hist_n<NT>(hist);  // ends with a barrier
   auto mark = [&](int e) { atomicOr(&sel[e >> 5], 1u << (e & 31)); };
+
+  // Short way: one digit of key - key(tau), scaled so that [tau, upper] fills the 2047 lower
+  // values of the digit (larger keys share 2047).  The list entries then spread over the whole
+  // histogram instead of piling up in the few bins a raw key prefix gives them; entries above
+  // the digit of the k-th largest are selected and the few inside it ranked against each other
+  // (score descending, index ascending).  More than 64 entries in that digit, or the catch-all
+  // digit: the three raw key digits below decide instead.
+  bool done = false;
+  if (c != k_eff) {
+    const uint32_t klo = order_key(tau[row]);
+    const uint32_t up = upper[row];
+    const uint32_t span = up > klo ? up - klo : 1u;
+    const int sh = __clz(span);
+    auto digit = [&](uint32_t key) {
+      const uint32_t x = key > klo ? key - klo : 0u;
+      return x > span ? (uint32_t)(kBins - 1) : (x << sh) >> 21;
+    };
+#pragma unroll
+    for (int u = 0; u < EPT; ++u)
+      if (ei[u] >= 0) atomicAdd(&hist[digit(ek[u])], 1);
+    __syncthreads();
+    find_threshold_bin_n<NT>(hist, k_eff, scan_scratch, thr);
+    const uint32_t d1 = thr[0];
+    const int need = thr[1], nb = thr[2];
+    if (nb <= 64 && d1 != kBins - 1) {   // block-uniform
+#pragma unroll
+      for (int u = 0; u < EPT; ++u) {
+        const uint32_t a = ei[u] >= 0 ? digit(ek[u]) : 0u;
+        if (ei[u] >= 0 && a > d1) mark(ei[u]);
+        const int b = wave_append(ei[u] >= 0 && a == d1, &b_len);
+        if (b >= 0) { bkey[b] = ek[u]; bidx[b] = ei[u]; }
+      }
+      __syncthreads();
+      if (tid < nb) {
+        const uint32_t key = bkey[tid];
+        const int e = bidx[tid];
+        int rank = 0;
+        for (int j = 0; j < nb; ++j) {
+          const uint32_t kj = bkey[j];
+          rank += (kj > key || (kj == key && bidx[j] < e)) ? 1 : 0;
+        }
+        if (rank < need) mark(e);
+      }
+      done = true;
+    } else {
+      __syncthreads();
+      zero_hist_n<NT>(hist);
+    }
+  }
 
   if (c == k_eff) {
 #pragma unroll
     for (int u = 0; u < EPT; ++u)
       if (ei[u] >= 0) mark(ei[u]);
-  } else {
+  } else if (!done) {
     // most significant digit first: 11 + 11 + 10 bits of the key
 #pragma unroll
     for (int u = 0; u < EPT; ++u)
@@ -309,7 +371,7 @@ __global__ __launch_bounds__(NT) void select_rows_kernel(
 namespace {
 
 struct Layout {
-  size_t S, sample, tau, count, row_flag, tile_flag, cand, total;
+  size_t S, sample, tau, upper, count, row_flag, tile_flag, cand, total;
   int m, cap, qwg, q_tiles;
 };
 
@@ -326,6 +388,7 @@ Layout layout(const Prob& p, bool routed, int k) {
   l.S = o;         o += up(rows * p.L * sizeof(float));
   l.sample = o;    o += up(rows * l.m * sizeof(float));
   l.tau = o;       o += up(rows * sizeof(float));
+  l.upper = o;     o += up(rows * sizeof(uint32_t));
   l.count = o;     o += up(rows * sizeof(int));
   l.row_flag = o;  o += up(rows * sizeof(int));
   l.tile_flag = o; o += up((size_t)p.n_seq * l.q_tiles * sizeof(int));
@@ -364,6 +427,7 @@ hipError_t launch_select(const Prob& p, int k_dtype, int q_dtype, const void* Q,
   float* S = reinterpret_cast<float*>(base + l.S);
   float* Ss = reinterpret_cast<float*>(base + l.sample);
   float* tau = reinterpret_cast<float*>(base + l.tau);
+  uint32_t* upper = reinterpret_cast<uint32_t*>(base + l.upper);
   int* count = reinterpret_cast<int*>(base + l.count);
   int* row_flag = reinterpret_cast<int*>(base + l.row_flag);
   int* tile_flag = reinterpret_cast<int*>(base + l.tile_flag);
@@ -373,7 +437,7 @@ hipError_t launch_select(const Prob& p, int k_dtype, int q_dtype, const void* Q,
   hipError_t e = launch_tile_mode(p, k_dtype, kTileSample, TileAux{}, Q, W, heads, K, kscale, Ss, st);
   if (e != hipSuccess) return e;
   select_threshold_kernel<<<(p.n_seq * p.n_q + 3) / 4, 256, 0, st>>>(
-      p, Ss, l.m, sample_rank(k), l.cap, l.qwg, l.q_tiles, tau, count, row_flag, tile_flag);
+      p, Ss, l.m, sample_rank(k), l.cap, l.qwg, l.q_tiles, tau, upper, count, row_flag, tile_flag);
   if ((e = hipGetLastError()) != hipSuccess) return e;
 
   TileAux filter;
@@ -394,8 +458,8 @@ hipError_t launch_select(const Prob& p, int k_dtype, int q_dtype, const void* Q,
       if (e != hipSuccess) return e;                                                                \
       attr = lds;                                                                                   \
     }                                                                                               \
-    select_rows_kernel<NT, EPT><<<rows, NT, lds, st>>>(p, cand, count, l.cap, k, l.qwg, l.q_tiles,  \
-                                                       idx, val, row_flag, tile_flag);              \
+    select_rows_kernel<NT, EPT><<<rows, NT, lds, st>>>(p, cand, count, tau, upper, l.cap, k, l.qwg, \
+                                                       l.q_tiles, idx, val, row_flag, tile_flag);   \
   } while (0)
   // thread count per row by list size (measured on MI355X: 512 for lists up to 5120
   // entries, 1024 above)

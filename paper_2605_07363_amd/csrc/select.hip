@@ -63,94 +63,77 @@ __device__ __forceinline__ float key_to_float(uint32_t key) {
 }
 
 // ---------------------------------------------------------------- threshold
-// Scans a wavefront's 2048-bin LDS histogram from the top: the bin d with
-// count(bins > d) < need <= count(bins >= d).  Lane l owns bins 2047 - 32 l ... 2016 - 32 l.
-// Returns d and leaves need - count(bins > d) in *rest.  All 64 lanes call it.
-__device__ __forceinline__ int wave_find_bin(const int* hist, int need, int* rest) {
-  const int lane = threadIdx.x & 63;
-  const int top = kBins - 1 - 32 * lane;
-  int local = 0;
-#pragma unroll
-  for (int i = 0; i < 32; ++i) local += hist[top - ((i + lane) & 31)];  // rotated: lanes on different banks
-  const int inc = wave_inclusive_scan(local);
-  int above = inc - local;
-  const bool mine = above < need && need <= inc;
-  int d = 0, r = 0;
-  if (mine) {
-    for (int i = 0; i < 32; ++i) {
-      const int c = hist[top - i];
-      if (need <= above + c) { d = top - i; r = need - above; break; }
-      above += c;
-    }
-  }
-  const int owner = __ffsll((long long)__ballot(mine)) - 1;
-  *rest = __shfl(r, owner);
-  return __shfl(d, owner);
-}
-
-// upper[row]: the top key of the first radix digit that holds the sampled score of rank r / 4,
-// a robust upper end of the interval in which the k-th largest score lies (select_rows_kernel
-// spreads its first digit over [tau, upper]).
-// One wavefront per row: tau[row] = a value at or just below the r-th largest of the
-// row's visible sampled scores (the lower edge of its 22-bit radix bin, i.e. within
-// 2^-13 relative), so at least r samples reach it.  Also clears the row's candidate
-// count and repair flags.
-__global__ __launch_bounds__(256) void select_threshold_kernel(
+// One workgroup of 256 threads per row: tau[row] = a value at or just below the r-th largest of
+// the row's visible sampled scores (the lower edge of its 22-bit radix bin, i.e. within 2^-13
+// relative), so at least r samples reach it.  upper[row]: the top key of the first radix digit
+// that holds the sampled score of rank r / 4, a robust upper end of the interval in which the
+// k-th largest score lies (select_rows_kernel spreads its first digit over [tau, upper]).  The
+// first 16 samples of every thread (4096 per row) stay in registers for both digit passes, all
+// their loads in flight together; longer rows read the rest again in the second pass.  Also
+// clears the row's candidate count and repair flags.
+constexpr int kThrThreads = 256;
+constexpr int kThrHeld = 16;
+__global__ __launch_bounds__(kThrThreads) void select_threshold_kernel(
     Prob p, const float* __restrict__ Ss, int m, int r, int cap, int qwg, int q_tiles,
     float* __restrict__ tau, uint32_t* __restrict__ upper, int* __restrict__ count,
     int* __restrict__ row_flag, int* __restrict__ tile_flag) {
-  __shared__ int hist_all[4][kBins];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int row = blockIdx.x * 4 + wave;
-  if (row >= p.n_seq * p.n_q) return;
+  __shared__ int hist[kBins];
+  __shared__ int hist2[kBins];
+  __shared__ int scan_scratch[32];
+  __shared__ int thr[3];
+  __shared__ int thr_up[3];
+  const int tid = threadIdx.x;
+  const int row = blockIdx.x;
   const int seq = row / p.n_q, t = row % p.n_q;
-  int* hist = hist_all[wave];
   const int n = visible(p, seq, t);
-  if (lane == 0) {
+  if (tid == 0) {
     count[row] = 0;
     row_flag[row] = 0;
     if (t % qwg == 0) tile_flag[seq * q_tiles + t / qwg] = 0;
   }
   if (n <= cap) {  // every visible key fits into the list
-    if (lane == 0) { tau[row] = -INFINITY; upper[row] = 0xFFFFFFFFu; }
+    if (tid == 0) { tau[row] = -INFINITY; upper[row] = 0xFFFFFFFFu; }
     return;
   }
   const int ns = n / kSampleStride;  // visible samples; ns > cap / 16 >= r
   const float* s = Ss + (size_t)row * m;
-  for (int i = lane; i < kBins; i += 64) hist[i] = 0;
-  __builtin_amdgcn_wave_barrier();
-  // eight loads per lane in flight before the first is used
+  float held[kThrHeld];
+#pragma unroll
+  for (int u = 0; u < kThrHeld; ++u) {
+    const int i = u * kThrThreads + tid;
+    held[u] = i < ns ? s[i] : 0.f;
+  }
+  for (int i = tid; i < kBins; i += kThrThreads) { hist[i] = 0; hist2[i] = 0; }
+  __syncthreads();
   auto scan = [&](auto f) {
-    for (int base = 0; base < ns; base += 512) {
+#pragma unroll
+    for (int u = 0; u < kThrHeld; ++u)
+      if (u * kThrThreads + tid < ns) f(order_key(held[u]));
+    for (int base = kThrHeld * kThrThreads; base < ns; base += 8 * kThrThreads) {
       float v[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        const int i = base + u * 64 + lane;
+        const int i = base + u * kThrThreads + tid;
         v[u] = i < ns ? s[i] : 0.f;
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u)
-        if (base + u * 64 + lane < ns) f(order_key(v[u]));
+        if (base + u * kThrThreads + tid < ns) f(order_key(v[u]));
     }
   };
   scan([&](uint32_t key) { atomicAdd(&hist[key >> 21], 1); });
-  __builtin_amdgcn_wave_barrier();
-  int need;
-  const uint32_t d1 = (uint32_t)wave_find_bin(hist, r, &need);
-  int unused;
-  const uint32_t d_up = (uint32_t)wave_find_bin(hist, max(r / 4, 1), &unused);  // a quarter of the way up
-  __builtin_amdgcn_wave_barrier();
-  for (int i = lane; i < kBins; i += 64) hist[i] = 0;
-  __builtin_amdgcn_wave_barrier();
+  __syncthreads();
+  find_threshold_bin_n<kThrThreads>(hist, r, scan_scratch, thr, max(r / 4, 1), thr_up);
+  const uint32_t d1 = (uint32_t)thr[0];
+  const int need = thr[1];
   scan([&](uint32_t key) {
-    if ((key >> 21) == d1) atomicAdd(&hist[(key >> 10) & 0x7FF], 1);
+    if ((key >> 21) == d1) atomicAdd(&hist2[(key >> 10) & 0x7FF], 1);
   });
-  __builtin_amdgcn_wave_barrier();
-  int rest;
-  const uint32_t d2 = (uint32_t)wave_find_bin(hist, need, &rest);
-  if (lane == 0) {
-    tau[row] = key_to_float((d1 << 21) | (d2 << 10));
-    upper[row] = (d_up << 21) | 0x1FFFFFu;
+  __syncthreads();
+  find_threshold_bin_n<kThrThreads>(hist2, need, scan_scratch, thr);
+  if (tid == 0) {
+    tau[row] = key_to_float((d1 << 21) | ((uint32_t)thr[0] << 10));
+    upper[row] = ((uint32_t)thr_up[0] << 21) | 0x1FFFFFu;
   }
 }
 
@@ -436,7 +419,7 @@ hipError_t launch_select(const Prob& p, int k_dtype, int q_dtype, const void* Q,
 
   hipError_t e = launch_tile_mode(p, k_dtype, kTileSample, TileAux{}, Q, W, heads, K, kscale, Ss, st);
   if (e != hipSuccess) return e;
-  select_threshold_kernel<<<(p.n_seq * p.n_q + 3) / 4, 256, 0, st>>>(
+  select_threshold_kernel<<<p.n_seq * p.n_q, kThrThreads, 0, st>>>(
       p, Ss, l.m, sample_rank(k), l.cap, l.qwg, l.q_tiles, tau, upper, count, row_flag, tile_flag);
   if ((e = hipGetLastError()) != hipSuccess) return e;
 

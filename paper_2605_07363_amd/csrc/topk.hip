@@ -29,6 +29,7 @@
 namespace misa {
 
 constexpr int kCap = 7000;          // boundary list capacity (entries); sized so two workgroups share a CU
+constexpr int kFew = 64;             // entries around the k-th largest that are ranked directly
 constexpr int kMaxRanges = 16;      // key ranges (workgroups) per row in the prefilter
 constexpr int kMinRange = 8192;     // shortest key range
 constexpr int kSampleLines = 256;   // sampled 16-element lines per row (at most)
@@ -300,6 +301,9 @@ __device__ __forceinline__ void topk_row(const Prob& p, const float* __restrict_
   __shared__ int scan_scratch[32];
   __shared__ int thr[3];
   __shared__ int list_len;
+  __shared__ int few_len;
+  __shared__ uint32_t fkey[kFew];
+  __shared__ int fidx[kFew];
 
   const int tid = threadIdx.x;
   const size_t row = (size_t)seq * p.n_q + t;
@@ -315,7 +319,7 @@ __device__ __forceinline__ void topk_row(const Prob& p, const float* __restrict_
   float* out_val = val ? val + row * k : nullptr;
 
   for (int i = tid; i < nwords; i += kTopkThreads) sel[i] = 0;
-  if (tid == 0) list_len = 0;
+  if (tid == 0) { list_len = 0; few_len = 0; }
   zero_hist(hist);
 
   bool done = false;
@@ -375,6 +379,28 @@ __device__ __forceinline__ void topk_row(const Prob& p, const float* __restrict_
       find_threshold_bin(hist, need, scan_scratch, thr);
       const uint32_t p22 = (d1 << 11) | (uint32_t)thr[0];
       need = thr[1];
+      const int nb = thr[2];
+      if (nb <= kFew) {
+        // ---- few list entries share the second threshold digit (the usual case): they are
+        //      ranked against each other by score, then index, instead of a third digit pass
+        for (int i = tid; i < len; i += kTopkThreads) {
+          const uint32_t key = lkey[i], kp = key >> 10;
+          if (kp > p22) atomicOr(&sel[lidx[i] >> 5], 1u << (lidx[i] & 31));
+          const int b = wave_append(kp == p22, &few_len);
+          if (b >= 0) { fkey[b] = key; fidx[b] = lidx[i]; }
+        }
+        __syncthreads();
+        if (tid < nb) {
+          const uint32_t key = fkey[tid];
+          const int e = fidx[tid];
+          int rank = 0;
+          for (int j = 0; j < nb; ++j) {
+            const uint32_t kj = fkey[j];
+            rank += (kj > key || (kj == key && fidx[j] < e)) ? 1 : 0;
+          }
+          if (rank < need) atomicOr(&sel[e >> 5], 1u << (e & 31));
+        }
+      } else {
       __syncthreads();
       zero_hist(hist);
       for (int i = tid; i < len; i += kTopkThreads) {
@@ -422,6 +448,7 @@ __device__ __forceinline__ void topk_row(const Prob& p, const float* __restrict_
           if ((e >> 10) == hi_digit && (e & 0x3FF) <= lo_digit) atomicOr(&sel[e >> 5], 1u << (e & 31));
         }
       }
+      }  // more than kFew entries in the second digit
       __syncthreads();
     } else {
       // ---- fallback: two more digit passes over the row, ties through a bitmap

@@ -89,3 +89,29 @@ def test_needles_and_topics_are_planted():
     seg = K[:WL.TOPIC_SEGMENT]
     seg = seg[np.abs(np.linalg.norm(seg, axis=1) - WL.NEEDLE_GAIN) > 0.15]
     assert np.linalg.norm(seg.mean(axis=0)) == pytest.approx(WL.TOPIC_KEY_AMPL, abs=0.08)
+
+
+def test_fp8_queries_fold_their_scale_into_the_gates():
+    # q_dtype = "e4m3": the generator stores codes only and multiplies the gates by the
+    # per-(query, head) scale.  Because ReLU is positively homogeneous, scoring the codes with the
+    # folded gates equals scoring the de-quantised queries (codes x scale) with the original
+    # gates (Eq. misa_score / Eq. dsa_score): checked with the oracle on every head.
+    wl8 = WL.scaled(WL.WORKLOADS["c1"], n_seq=1, L=400, q_dtype="e4m3", needles=0)
+    wl16 = WL.scaled(wl8, q_dtype="bf16")
+    a, b = WL.make_inputs(wl8, seed=3), WL.make_inputs(wl16, seed=3)
+    assert a["Q"].dtype == np.uint8 and a["Q"].shape == b["Q"].shape
+    np.testing.assert_array_equal(a["K"], b["K"])                   # same random stream otherwise
+    codes = O.e4m3fn_decode_table()[a["Q"][0, 0]]                    # [H, d] values of the codes
+    w_folded = a["W"][0, 0].astype(np.float64)
+    w_plain = b["W"][0, 0].astype(np.float64)
+    scale = w_folded / w_plain                                       # what the generator folded in
+    assert np.all(scale > 0)
+    K = O.dequantise(a["K"][0], wl8.k_dtype)
+    heads = np.arange(wl8.H)
+    s_codes = O.score_tokens(codes, w_folded, heads, K)
+    s_values = O.score_tokens(codes * scale[:, None], w_plain, heads, K)
+    np.testing.assert_allclose(s_codes, s_values, rtol=1e-6, atol=1e-9)
+    # and the codes times their scale reproduce the bf16-free original queries to fp8 precision
+    q_orig = O.dequantise(b["Q"][0, 0], "bf16")
+    amax = np.abs(q_orig).max(axis=-1, keepdims=True)
+    assert np.all(np.abs(codes * scale[:, None] - q_orig) <= amax * (2.0 ** -4 + 2.0 ** -8))

@@ -73,6 +73,20 @@ hipError_t launch_hisa(const Prob& p, int k_dtype, int q_dtype, const void* Q, c
                        const float* Kp, const void* K, const float* kscale, int m, int k, int* blocks,
                        int* idx, float* val, void* ws, hipStream_t st);
 
+// Raises a kernel's dynamic-LDS limit when a launch needs more than any launch before it on the
+// current device (`seen` is the caller's per-kernel record, one entry per device; devices past
+// the 64th get the attribute set on every launch).
+inline hipError_t ensure_dynamic_lds(const void* func, size_t lds, size_t (&seen)[64]) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < 64;
+  if (tracked && lds <= seen[dev]) return hipSuccess;
+  e = hipFuncSetAttribute(func, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e == hipSuccess && tracked) seen[dev] = lds;
+  return e;
+}
+
 // fp8 query codes -> bf16 (convert.hip); n_elems a multiple of 128.
 hipError_t launch_widen_queries(const void* q8, void* q16, size_t n_elems, hipStream_t st);
 

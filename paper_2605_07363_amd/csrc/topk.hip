@@ -574,17 +574,11 @@ size_t topk_ws_bytes(const Prob& p, int k) {
 
 template <int WHICH>  // 0: topk_kernel<false>, 1: topk_kernel<true>, 2: topk_only_kernel
 static hipError_t set_lds_limit(size_t lds) {
-  static size_t attr_bytes = 48 * 1024;  // default dynamic LDS limit
-  if (lds > attr_bytes) {
-    const void* f = WHICH == 0 ? reinterpret_cast<const void*>(topk_kernel<false>)
-                  : WHICH == 1 ? reinterpret_cast<const void*>(topk_kernel<true>)
-                               : reinterpret_cast<const void*>(topk_only_kernel);
-    hipError_t e = hipFuncSetAttribute(f,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_bytes = lds;
-  }
-  return hipSuccess;
+  static size_t seen[64] = {};
+  const void* f = WHICH == 0 ? reinterpret_cast<const void*>(topk_kernel<false>)
+                : WHICH == 1 ? reinterpret_cast<const void*>(topk_kernel<true>)
+                             : reinterpret_cast<const void*>(topk_only_kernel);
+  return ensure_dynamic_lds(f, lds, seen);
 }
 
 hipError_t launch_topk(const Prob& p, const float* S, int row_len, int k, const int* map, int* idx,

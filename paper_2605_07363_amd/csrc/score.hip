@@ -749,7 +749,7 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
   // Row m of tile rt is head rt*32 + m; half-wave hf holds components 64 hf .. 64 hf + 63,
   // k-step ks the eight from 64 hf + 8 ks (the key fragments use the same mapping).
   Frag a[RT][8];
-  float gate[RT][16];
+  __shared__ float s_gate[2][RT * 16];   // [half-wave][accumulator register]: gates of the rows a lane holds
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
     const int head = rt * 32 + col;
@@ -759,11 +759,11 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
       const uint4 v = *reinterpret_cast<const uint4*>(src + 8 * ks);
       a[rt][ks].u = head < p.H ? v : make_uint4(0, 0, 0, 0);
     }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int hd = rt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-      gate[rt][r] = hd < p.H ? W[qrow * p.H + hd] : 0.f;
-    }
+  }
+  if (threadIdx.x < 2 * RT * 16) {
+    const int h2 = threadIdx.x / (RT * 16), e = threadIdx.x % (RT * 16), rt = e / 16, r = e % 16;
+    const int hd = rt * 32 + 8 * (r >> 2) + 4 * h2 + (r & 3);
+    s_gate[h2][e] = hd < p.H ? W[qrow * p.H + hd] : 0.f;
   }
 
   // Loads are unconditional and branch-free (slot and row clamped), so the number
@@ -807,7 +807,7 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-      for (int q = 0; q < 16; ++q) sum = fmaf(gate[rt][q], relu(acc[rt][q]), sum);
+      for (int q = 0; q < 16; ++q) sum = fmaf(s_gate[hf][rt * 16 + q], relu(acc[rt][q]), sum);
     sum += __shfl_xor(sum, 32);
     const int slot = c0 + col;
     if (hf == 0 && slot < c_end) orow[slot] = r.s >= 0 ? sum * r.scale : -INFINITY;
@@ -815,7 +815,7 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
 
   // kDepth register buffers: the loads of a step are issued kDepth - 1 steps before they are
   // used (a step of one wavefront is far shorter than the latency of a gathered row).
-  constexpr int kDepth = KDT == MISA_BF16 ? 3 : 4;
+  constexpr int kDepth = 2;
   Raw buf[kDepth];
   int c0 = c_begin + wave * 32;
   __builtin_amdgcn_s_waitcnt(0);  // the query operand has landed; in-loop waits concern only loop loads

@@ -124,9 +124,8 @@ __global__ __launch_bounds__(256) void route_tile_kernel(Prob p, int splits,
   const int per = (p.M + splits - 1) / splits;
   const int b_lo = split * per, b_hi = min(b_lo + per, p.M);
 
-  // stationary operand and, per accumulator register, the number of pooled blocks its row may use
+  // stationary operand
   RFrag a[2][8];
-  int nb[2][16];
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt) {
     const int row = row0 + rt * 32 + col;
@@ -136,31 +135,29 @@ __global__ __launch_bounds__(256) void route_tile_kernel(Prob p, int splits,
       const uint4 v = *reinterpret_cast<const uint4*>(src + ks * 16);
       a[rt][ks].u = row < rows_per_seq ? v : make_uint4(0, 0, 0, 0);
     }
-    // the 16 rows of this lane belong to at most a few queries: the block count is
-    // recomputed only when the query changes
-    int t_prev = -1, nb_prev = 0;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int rr = row0 + rt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-      int v = 0;
-      if (rr < rows_per_seq) {
-        const int t = rr / p.H;
-        if (t != t_prev) { nb_prev = pooled_blocks(visible(p, seq, t), len, p.B); t_prev = t; }
-        v = nb_prev;
-      }
-      nb[rt][r] = v;
-    }
   }
-  int nb_max = 0;
+  // per row of the wavefront, the number of pooled blocks it may use (its own prefix, cut at
+  // the end of this split); kept in LDS because only tiles on the causal edge need it
+  __shared__ int s_nb[4][64];
+  int nb_lane = 0;
+  {
+    const int rr = row0 + lane;
+    if (rr < rows_per_seq) nb_lane = min(pooled_blocks(visible(p, seq, rr / p.H), len, p.B), b_hi);
+    s_nb[wave][lane] = nb_lane;
+  }
+  int nb_max = nb_lane, nb_min = nb_lane;
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) nb_max = max(nb_max, nb[rt][r]);
+  for (int o = 32; o >= 1; o >>= 1) {
+    nb_max = max(nb_max, __shfl_xor(nb_max, o));
+    nb_min = min(nb_min, __shfl_xor(nb_min, o));
+  }
+  // tiles that end at or before this limit are visible in full to every row of the wavefront
+  const int b_full = __builtin_amdgcn_readfirstlane(nb_min);
   // the block range this workgroup must visit: up to the largest count of any of its rows
   __shared__ int s_stop;
   if (tid == 0) s_stop = 0;
   __syncthreads();
-  atomicMax(&s_stop, min(nb_max, b_hi));
+  if (lane == 0) atomicMax(&s_stop, nb_max);
   __syncthreads();
   const int b_stop = s_stop;
 
@@ -227,12 +224,24 @@ __global__ __launch_bounds__(256) void route_tile_kernel(Prob p, int splits,
           acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, bl.v, acc[rt], 0, 0, 0);
         }
       }
-      const int b = b0 + col;
+      if (b0 + kRouteKT <= b_full) {
 #pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
+        for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          sum[rt][r] += (b < nb[rt][r] && b < b_hi) ? relu(acc[rt][r]) : 0.f;
+          for (int r = 0; r < 16; ++r) sum[rt][r] += relu(acc[rt][r]);
+      } else {
+        const int b = b0 + col;
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int4 nb = *reinterpret_cast<const int4*>(&s_nb[wave][rt * 32 + 8 * g + 4 * hf]);
+            sum[rt][4 * g + 0] += b < nb.x ? relu(acc[rt][4 * g + 0]) : 0.f;
+            sum[rt][4 * g + 1] += b < nb.y ? relu(acc[rt][4 * g + 1]) : 0.f;
+            sum[rt][4 * g + 2] += b < nb.z ? relu(acc[rt][4 * g + 2]) : 0.f;
+            sum[rt][4 * g + 3] += b < nb.w ? relu(acc[rt][4 * g + 3]) : 0.f;
+          }
+      }
     }
     if (more) store_tile(buf ^ 1);
     __syncthreads();

@@ -542,7 +542,9 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(Prob p, const float*
                                                             const int* __restrict__ pre, int rlen,
                                                             bool all_slots) {
   extern __shared__ uint32_t dyn[];
-  topk_row<CAND>(p, S, row_len, k, map, idx, val, pre, rlen, blockIdx.x, blockIdx.y, dyn, all_slots);
+  // queries in descending order: under a causal mask the late ones have the longest rows, and
+  // the workgroups with the most work should start first
+  topk_row<CAND>(p, S, row_len, k, map, idx, val, pre, rlen, gridDim.x - 1 - blockIdx.x, blockIdx.y, dyn, all_slots);
 }
 
 // Only the rows r with only[r] != 0 (rows another path could not finish).  Normally

@@ -24,7 +24,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
 # HBM bytes per launch of the score kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # plain device copy of known size in the same run (profiles/score_stream_*_hbm_traffic.md).
-MEASURED_TRAFFIC_BYTES = {"c1": 548.7e6, "c3": 571.0e6}
+MEASURED_TRAFFIC_BYTES = {"c1": 548.8e6, "c3": 571.0e6}
 
 DESCRIPTIONS = {
     "c0": "tiny decode: 1 seq x 1 query, L=4096, H=64, h=8, B=64, k=256, fp32",

@@ -317,7 +317,7 @@ constexpr int kKT = 64;  // keys per LDS tile
 constexpr int kKP = 17;  // 16-byte slots per key row in LDS: 16 of data + 1 of padding
 // Queries per sequence from which the tiled matrix-core kernel is used.
 constexpr int kTileMinQueries = 8;
-constexpr int kStageCap = 256;  // filter mode: staged candidates per wavefront and pair of queries
+constexpr int kStageCap = 320;  // filter mode: staged candidates per wavefront and pair of queries
 
 // MODE kTileStore: scores of all keys go to S [rows, L].
 // MODE kTileSample: only one key of every group of kSampleStride consecutive
@@ -459,7 +459,7 @@ __device__ __forceinline__ void score_tile_body(
   // filter mode: thresholds of this lane's queries and the lengths of the wavefront's
   // staging lists (wavefront-uniform, so they live in scalar registers)
   float tauv[NQL];
-  int cnt[NQL];
+  int cnt[NQL], cnt_up[NQL];  // entries of a staging list; those of the upper half-wave's query among them
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   int n_min = 0x7FFFFFFF;
 #pragma unroll
@@ -469,6 +469,7 @@ __device__ __forceinline__ void score_tile_body(
     qn[j] = ok ? nvis[qi] : -1;   // -1: query does not exist, nothing is stored
     qoff[j] = (uint32_t)qi * (uint32_t)LT;
     cnt[j] = 0;
+    cnt_up[j] = 0;
     tauv[j] = FILTER ? s_tau[qi] : 0.f;
   }
   // Moves staging list j (the candidates of the two queries in accumulator slot j of the
@@ -476,25 +477,18 @@ __device__ __forceinline__ void score_tile_body(
   auto flush_list = [&](int j) {
     const int c = cnt[j];
     const int2* src = stg + (wave_u * NQL + j) * kStageCap;
-    // entries of each query: first the totals, then one atomic per query reserves the room
-    int tot0 = 0, tot1 = 0;
-    for (int i0 = 0; i0 < c; i0 += 64) {
-      const bool in = i0 + lane < c;
-      const bool up = in && src[min(i0 + lane, c - 1)].x < 0;
-      const int n_up = __popcll(__ballot(up));
-      tot1 += n_up;
-      tot0 += min(64, c - i0) - n_up;
-    }
+    // the totals of the two queries are kept while appending, so the atomics that reserve the
+    // room (one per query, lanes 0 and 1) go out first and the list is read while they travel
     const int qi = wave_u * QW + (HS == 8 ? (j >> 1) * 4 + (lane & 1) * 2 + (j & 1) : (HS == 16 ? j * 2 + (lane & 1) : (lane & 1)));
     const size_t my_row = (size_t)seq * p.n_q + q_base + qi;   // lanes 0 and 1: the two queries
     int base = 0;
-    const int mine = lane == 0 ? tot0 : tot1;
+    const int mine = lane == 0 ? c - cnt_up[j] : cnt_up[j];
     if (lane < 2 && mine > 0) base = atomicAdd(&aux.count[my_row], mine);
+    int2 e = src[min(lane, c - 1)];
     int run0 = __shfl(base, 0), run1 = __shfl(base, 1);
     const long long row0 = __shfl((long long)my_row, 0), row1 = __shfl((long long)my_row, 1);
     for (int i0 = 0; i0 < c; i0 += 64) {
       const bool in = i0 + lane < c;
-      int2 e = src[min(i0 + lane, c - 1)];
       const bool up = in && e.x < 0, down = in && e.x >= 0;
       const unsigned long long mu = __ballot(up), md = __ballot(down);
       const int pos = up ? run1 + __popcll(mu & ((1ull << lane) - 1ull))
@@ -503,8 +497,10 @@ __device__ __forceinline__ void score_tile_body(
       if (in && pos < aux.cap) aux.cand[(up ? row1 : row0) * aux.cap + pos] = e;
       run1 += __popcll(mu);
       run0 += __popcll(md);
+      if (i0 + 64 < c) e = src[min(i0 + 64 + lane, c - 1)];
     }
     cnt[j] = 0;
+    cnt_up[j] = 0;
   };
 
   for (int i = 0; i < QWG; ++i) n_min = min(n_min, q_base + i < p.n_q ? nvis[i] : -1);
@@ -556,6 +552,7 @@ __device__ __forceinline__ void score_tile_body(
         if (pass)
           stg[(wave_u * NQL + j) * kStageCap + slot] = make_int2(key | (int)((uint32_t)hf << 31), __float_as_int(out[j]));
         cnt[j] += __popcll(m);
+        cnt_up[j] += __popc((uint32_t)(m >> 32));
       }
     } else if (PLAIN) {
 #pragma unroll
@@ -608,21 +605,69 @@ __device__ __forceinline__ void score_tile_body(
       }
     finish(plain_tag, out, key, scale);
   };
-  // Filter mode leaves the order inside a step to the compiler's scheduler (its compare /
-  // ballot / staged-write tail does not fit the fixed pattern and measured slower with it),
-  // with a request to spread the vector work between the matrix instructions.
-  auto loose_step = [&](auto plain_tag, f32x16 (&acc_new)[RT], int tile, const f32x16 (&acc_old)[RT],
-                        int key, float scale) {
-    mfma_tile(acc_new, tile);
-    epilogue(plain_tag, acc_old, key, scale);
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);        // DS reads
+  // Filter mode uses the same fixed pattern, with the list bookkeeping of a column tile put off
+  // by one step: a step ends with the compare and ballot of its own sums only (the masks stay
+  // in scalar registers, the sums in NQL vector registers), and the slot arithmetic and the
+  // staged writes of those candidates sit between the first matrix instructions of the next
+  // step instead of after the last one, where nothing of this wavefront would cover them.
+  unsigned long long pend_m[NQL];
+  float pend_out[NQL];
+  int pend_key = 0;  // the lane's key of the step the pending sums are from
 #pragma unroll
-    for (int i = 0; i < 8 * RT; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
-      __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);     // ten VALU
-      __builtin_amdgcn_sched_group_barrier(0x004, 2, 0);      // ballot bookkeeping
-      if (i % 4 == 3) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // a staged candidate write
+  for (int j = 0; j < NQL; ++j) {
+    pend_m[j] = 0;
+    pend_out[j] = 0.f;
+  }
+  auto append_pending = [&](int j) {
+    const unsigned long long m = pend_m[j];
+    const int slot = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, cnt[j]));
+    if ((m >> lane) & 1ull)
+      stg[(wave_u * NQL + j) * kStageCap + slot] = make_int2(pend_key | (int)((uint32_t)hf << 31), __float_as_int(pend_out[j]));
+    cnt[j] += __popcll(m);
+    cnt_up[j] += __popc((uint32_t)(m >> 32));
+  };
+  auto drain_pending = [&]() {
+#pragma unroll
+    for (int j = 0; j < NQL; ++j) {
+      append_pending(j);
+      pend_m[j] = 0;
     }
+  };
+  auto filter_step = [&](auto plain_tag, f32x16 (&acc_new)[RT], int tile, const f32x16 (&acc_old)[RT],
+                         int key, float scale) {
+    constexpr bool PLAIN = decltype(plain_tag)::value;
+    Frag b[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) b[ks].u = (&ktile[0][0])[frag0 + tile + 2 * ks];
+    float out[NQL];
+#pragma unroll
+    for (int j = 0; j < NQL; ++j) out[j] = 0.f;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        if (ks == 0) {
+          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          acc_new[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b[ks].v, zero, 0, 0, 0);
+        } else {
+          acc_new[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b[ks].v, acc_new[rt], 0, 0, 0);
+        }
+        const int e = (ks * RT + rt) * 2;
+        head_term(out, acc_old, e / 16, e % 16);
+        head_term(out, acc_old, (e + 1) / 16, (e + 1) % 16);
+        if (ks * RT + rt < NQL) append_pending(ks * RT + rt);
+        asm volatile("" : "+v"(out[HS == 8 ? (e / 16) * 2 + ((e % 16) >> 3) : (HS == 16 ? e / 16 : 0)]));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+    for (int j = 0; j < NQL; ++j) {
+      const float o = KDT == MISA_FP8_E4M3 ? out[j] * scale : out[j];
+      const bool pass = o >= tauv[j] && (PLAIN || (key < k_end && key < qn[j]));
+      pend_m[j] = __ballot(pass);
+      pend_out[j] = o;
+    }
+    pend_key = key;
   };
   using Yes = std::true_type;
   using No = std::false_type;
@@ -648,17 +693,25 @@ __device__ __forceinline__ void score_tile_body(
     auto body = [&](auto tag, int i) {
       const int buf = i & 1, k0 = k_begin + i * kKT;
       const bool more = i + 1 < n_tiles;
-      if (FILTER) loose_step(tag, accB, (buf * 64 + 32) * kKP, accA, k0 + col, scaleA);
+      if (FILTER) filter_step(tag, accB, (buf * 64 + 32) * kKP, accA, k0 + col, scaleA);
       else tile_step(tag, accB, (buf * 64 + 32) * kKP, accA, k0 + col, scaleA);
       if (KDT == MISA_FP8_E4M3) scaleB = kscl[buf][32 + col];
       if (more) MISA_TILE_STORE(buf ^ 1);
       __syncthreads();
       if (more) {
         if (i + 2 < n_tiles) MISA_TILE_LOAD(k0 + 2 * kKT);
-        if (FILTER) loose_step(tag, accA, (buf ^ 1) * 64 * kKP, accB, k0 + 32 + col, scaleB);
+        if (FILTER) filter_step(tag, accA, (buf ^ 1) * 64 * kKP, accB, k0 + 32 + col, scaleB);
         else tile_step(tag, accA, (buf ^ 1) * 64 * kKP, accB, k0 + 32 + col, scaleB);
         if (KDT == MISA_FP8_E4M3) scaleA = kscl[buf ^ 1][col];
       } else {
+        if (FILTER) {
+          // the last column tile is finished at once: its entries (up to kKT per list) come
+          // on top of the two steps' worth the body has appended already
+          drain_pending();
+#pragma unroll
+          for (int j = 0; j < NQL; ++j)
+            if (cnt[j] > kStageCap - kKT) flush_list(j);
+        }
         epilogue(tag, accB, k0 + 32 + col, scaleB);
       }
       if (FILTER) {
@@ -671,7 +724,7 @@ __device__ __forceinline__ void score_tile_body(
     const int n_plain = min(n_tiles, max(0, (plain_end - k_begin) / kKT));
     for (int i = 0; i < n_plain; ++i) body(Yes{}, i);
     for (int i = n_plain; i < n_tiles; ++i) body(No{}, i);
-    if (FILTER) {
+    if (FILTER) {  // (the last body has drained the pending sums)
 #pragma unroll
       for (int j = 0; j < NQL; ++j)
         if (cnt[j] > 0) flush_list(j);

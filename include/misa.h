@@ -55,7 +55,8 @@
  *   be validated on the host: out-of-range values are clamped or ignored as
  *   described per call, they never cause out-of-bounds accesses.
  * - Limits of this build: d == 128, 1 <= H <= 64, 1 <= h <= H,
- *   L <= 524288, k <= 16384, q_dtype in {F32, BF16}.
+ *   L <= 524288, k <= 16384; keys in F32, BF16 or FP8_E4M3 (with scales),
+ *   queries in F32, BF16 or FP8_E4M3 (codes without scales, see "fp8 queries").
  */
 #ifndef MISA_H
 #define MISA_H
@@ -78,7 +79,7 @@ typedef enum misa_status {
 typedef enum misa_dtype {
   MISA_F32 = 0,
   MISA_BF16 = 1,
-  MISA_FP8_E4M3 = 2 /* OCP FP8 E4M3 ("e4m3fn": bias 7, max 448, no infinity), keys only */
+  MISA_FP8_E4M3 = 2 /* OCP FP8 E4M3 ("e4m3fn": bias 7, max 448, no infinity)            */
 } misa_dtype;
 
 typedef enum misa_op {

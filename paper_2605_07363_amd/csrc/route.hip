@@ -377,6 +377,7 @@ __global__ __launch_bounds__(128) void route_finalize_kernel(
   __shared__ float Es[kMaxH];
   __shared__ int sel[kMaxH];
   __shared__ float sred[4][kMaxH];
+  __shared__ float sdot[kMaxH];
   using KV = Vec16<KDT>;
   const int t = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
   const int n = visible(p, seq, t), len = seq_length(p, seq);
@@ -395,14 +396,15 @@ __global__ __launch_bounds__(128) void route_finalize_kernel(
       const f32x2 pr = __builtin_amdgcn_cvt_pk_f32_fp8(w >> ((tid & 2) * 8), false);
       return pr[tid & 1] * kscale[slot];
     };
-    // rows are added in order; eight loads are in flight at a time
+    // rows are added in order; 32 loads are in flight at a time (the workgroup's run time is the
+    // latency of these rounds, and a block of 64 has at most two of them)
     float s = 0.f;
-    for (int row = nfull * p.B; row < n; row += 8) {
-      float v[8];
+    for (int row = nfull * p.B; row < n; row += 32) {
+      float v[32];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = key_component(min(row + u, n - 1));
+      for (int u = 0; u < 32; ++u) v[u] = key_component(min(row + u, n - 1));
 #pragma unroll
-      for (int u = 0; u < 8; ++u) s += row + u < n ? v[u] : 0.f;
+      for (int u = 0; u < 32; ++u) s += row + u < n ? v[u] : 0.f;
     }
     tailk[tid] = s / (float)r;
   }
@@ -426,23 +428,34 @@ __global__ __launch_bounds__(128) void route_finalize_kernel(
   }
   __syncthreads();
 
+  if (tail) {
+    // q_j . (tail mean) for all heads: the query's H rows are one contiguous piece, read in
+    // 16-byte chunks in thread order; the CPH consecutive lanes that hold a head's chunks add
+    // their partial products with a butterfly, and the first of them keeps the sum.
+    using QV = Vec16<QDT>;
+    constexpr int CPH = kD / QV::N;  // chunks per head row: 32 (fp32) or 16 (bf16)
+    const char* qrow = static_cast<const char*>(Q) + ((size_t)seq * p.n_q + t) * p.H * QV::ROW_BYTES;
+    const int total = p.H * CPH, part_of = tid % CPH;
+    for (int base = 0; base < total; base += 128) {
+      const int c = base + tid;
+      float v[QV::N], d = 0.f;
+      if (c < total) {
+        QV::load(qrow + (size_t)c * 16, v);
+#pragma unroll
+        for (int e = 0; e < QV::N; ++e) d = fmaf(v[e], tailk[part_of * QV::N + e], d);
+      }
+#pragma unroll
+      for (int o = CPH / 2; o >= 1; o >>= 1) d += __shfl_xor(d, o);
+      if (part_of == 0 && c < total) sdot[c / CPH] = d;
+    }
+    __syncthreads();
+  }
+
   if (tid < p.H) {
     const size_t qi = ((size_t)seq * p.n_q + t) * p.H + tid;
     float s = sred[0][tid] + sred[1][tid];
     if (p.H <= 32) s += sred[2][tid] + sred[3][tid];
-    if (tail) {
-      float qv[kD];
-      load_query_head<QDT>(Q, qi, qv);
-      float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
-#pragma unroll
-      for (int c = 0; c < kD; c += 4) {
-        d0 = fmaf(qv[c], tailk[c], d0);
-        d1 = fmaf(qv[c + 1], tailk[c + 1], d1);
-        d2 = fmaf(qv[c + 2], tailk[c + 2], d2);
-        d3 = fmaf(qv[c + 3], tailk[c + 3], d3);
-      }
-      s += fmaxf((d0 + d1) + (d2 + d3), 0.f);
-    }
+    if (tail) s += fmaxf(sdot[tid], 0.f);
     const float e = Mn > 0 ? fabsf(W[qi]) * s / (float)Mn : 0.f;
     Es[tid] = e;
     if (E) E[qi] = e;

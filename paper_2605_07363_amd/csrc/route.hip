@@ -162,21 +162,23 @@ __global__ __launch_bounds__(256) void route_tile_kernel(Prob p, int splits,
   const int b_stop = s_stop;
 
   const float* kp_seq = Kp + (size_t)seq * p.M * kD;
-  float4 stage[4];
-  auto load_tile = [&](int b0) {
+  float4 stage[2][4];  // two sets: with CP == 1 tiles are requested two iterations ahead
+  auto load_tile = [&](int b0, auto set_tag) {
+    constexpr int SET = decltype(set_tag)::value;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int e = tid + 256 * i;               // float4 index inside the 32 x 128 tile
       const int row = e >> 5;
-      stage[i] = *reinterpret_cast<const float4*>(kp_seq + (size_t)min(b0 + row, p.M - 1) * kD + (e & 31) * 4);
+      stage[SET][i] = *reinterpret_cast<const float4*>(kp_seq + (size_t)min(b0 + row, p.M - 1) * kD + (e & 31) * 4);
     }
   };
-  auto store_tile = [&](int buf) {
+  auto store_tile = [&](int buf, auto set_tag) {
+    constexpr int SET = decltype(set_tag)::value;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int e = tid + 256 * i;
       const int row = e >> 5, c4 = e & 31;        // c4: group of 4 components
-      const float x[4] = {stage[i].x, stage[i].y, stage[i].z, stage[i].w};
+      const float x[4] = {stage[SET][i].x, stage[SET][i].y, stage[SET][i].z, stage[SET][i].w};
       uint32_t hi[2], lo[2];
       split_pair(x[0], x[1], hi[0], lo[0]);
       split_pair(x[2], x[3], hi[1], lo[1]);
@@ -193,17 +195,26 @@ __global__ __launch_bounds__(256) void route_tile_kernel(Prob p, int splits,
 #pragma unroll
     for (int r = 0; r < 16; ++r) sum[rt][r] = 0.f;
 
+  using Set0 = std::integral_constant<int, 0>;
+  using Set1 = std::integral_constant<int, 1>;
   int buf = 0;
   if (b_lo < b_stop) {
-    load_tile(b_lo);
-    store_tile(0);
+    load_tile(b_lo, Set1{});
+    store_tile(0, Set1{});
+    if (CP == 1) load_tile(b_lo + kRouteKT, Set0{});  // staged during the first iteration
   }
   __builtin_amdgcn_s_waitcnt(0);  // prologue loads have landed; in-loop waits concern only loop loads
   __syncthreads();
   int it = 0;
-  for (int b0 = b_lo; b0 < b_stop; b0 += kRouteKT, ++it) {
-    const bool more = b0 + kRouteKT < b_stop;
-    if (more) load_tile(b0 + kRouteKT);
+  // One iteration.  CP == 1: the set named by set_tag holds the next tile (requested an iteration
+  // ago) and is staged between the matrix instructions, the tile after it is requested into the
+  // other set.  Otherwise one set is loaded at the top and staged at the bottom.  Tiles past the
+  // last are requested and staged too, with clamped addresses (never read): the body stays one
+  // scheduling region.
+  auto iteration = [&](int b0, auto set_tag) {
+    constexpr int SET = decltype(set_tag)::value;
+    if (CP == 1) load_tile(b0 + 2 * kRouteKT, std::integral_constant<int, SET ^ 1>{});
+    else load_tile(b0 + kRouteKT, Set0{});
     if (it % CP == phase) {
       f32x16 acc[2];
 #pragma unroll
@@ -224,6 +235,12 @@ __global__ __launch_bounds__(256) void route_tile_kernel(Prob p, int splits,
           acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, bl.v, acc[rt], 0, 0, 0);
         }
       }
+      if (CP == 1) {
+        // staging the next tile (split into pieces, LDS writes) needs nothing from these matrix
+        // instructions and its data arrived an iteration ago: it sits in the same scheduling
+        // region, ahead of the sums that have to wait for them
+        store_tile(buf ^ 1, set_tag);
+      }
       if (b0 + kRouteKT <= b_full) {
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt)
@@ -243,9 +260,17 @@ __global__ __launch_bounds__(256) void route_tile_kernel(Prob p, int splits,
           }
       }
     }
-    if (more) store_tile(buf ^ 1);
+    if (CP != 1) store_tile(buf ^ 1, Set0{});
     __syncthreads();
     buf ^= 1;
+    ++it;
+  };
+  for (int b0 = b_lo; b0 < b_stop;) {
+    iteration(b0, Set0{});
+    b0 += kRouteKT;
+    if (b0 >= b_stop) break;
+    if (CP == 1) iteration(b0, Set1{}); else iteration(b0, Set0{});
+    b0 += kRouteKT;
   }
 
   // sum over the 32 block columns of each half-wave, then one lane per row writes

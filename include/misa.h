@@ -27,10 +27,13 @@
  * Conventions common to all calls
  * -------------------------------
  * - Every data pointer is DEVICE memory owned by the caller unless it is
- *   marked "host".  The library allocates nothing, frees nothing and keeps
- *   no state between calls.  Scratch memory is passed in as (ws, ws_bytes);
- *   ask misa_workspace_bytes() for the size (it may be 0, then ws may be
- *   NULL).  ws must be 256-byte aligned.
+ *   marked "host".  The library allocates nothing and frees nothing.  No
+ *   result depends on an earlier call: the only things kept between calls
+ *   are the thread-local error text, a per-device record of the dynamic-LDS
+ *   limit already raised for a kernel (atomic; host threads may call
+ *   concurrently) and the scratch array of misa_route_heads_static.  Scratch
+ *   memory is passed in as (ws, ws_bytes); ask misa_workspace_bytes() for the
+ *   size (it may be 0, then ws may be NULL).  ws must be 256-byte aligned.
  * - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *   Calls only enqueue work on it; they never synchronise the host.
  * - Tensors are dense, row-major, innermost dimension contiguous:
@@ -187,6 +190,28 @@ misa_status misa_pool_keys_update(const misa_problem* p, const void* K, const fl
 misa_status misa_route_heads(const misa_problem* p, const void* Q, const float* W,
                              const float* Kp, const void* K, const float* kscale,
                              int32_t* heads, float* E, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * misa_route_heads for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and error behaviour as
+ * misa_route_heads, but the partial sums of the block tiles (and the widened
+ * copy of fp8 queries) live in an array of MISA_ROUTE_STATIC_SCRATCH_BYTES bytes
+ * that is part of the library's device code; every GPU the library runs on
+ * holds one copy of it until the process ends.  The call allocates and frees
+ * nothing.  Problems whose misa_workspace_bytes(p, MISA_OP_ROUTE, 0) exceeds
+ * MISA_ROUTE_STATIC_SCRATCH_BYTES are rejected with MISA_ERR_UNSUPPORTED before
+ * anything is launched (4 MiB covers decode batches of up to 256 sequences and
+ * prefill chunks of up to 4096 bf16 queries).  All calls on one GPU share that
+ * GPU's array: calls that may overlap in time on one GPU (different streams or
+ * host threads) race on it and must be serialised by the caller; nothing in
+ * the array has to be cleared between calls (every word read is written first
+ * by the same call).
+ */
+#define MISA_ROUTE_STATIC_SCRATCH_BYTES (4u << 20)
+misa_status misa_route_heads_static(const misa_problem* p, const void* Q, const float* W,
+                                    const float* Kp, const void* K, const float* kscale,
+                                    int32_t* heads, float* E, void* stream);
 
 /*
  * Head routing with one of the two content-free scores that the appendix

@@ -1,11 +1,17 @@
 // C ABI of the MISA indexer library: argument validation, workspace sizing,
 // error reporting and dispatch to the kernel launchers.  See include/misa.h
 // for the contract of every entry point.
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
 
 #include "kernels.h"
+
+// Scratch of misa_route_heads_static: the router's partial sums (and, for fp8 queries, their
+// widened copy) live here instead of in a caller workspace.  Every GPU the library runs on
+// holds its own copy of the array, at its own address, until the process ends.
+static __device__ __align__(256) unsigned char scratch[MISA_ROUTE_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -188,6 +194,42 @@ misa_status misa_route_heads(const misa_problem* p, const void* Q, const float* 
   return hip_result(misa::launch_route(pr, p->k_dtype, qv.q_dtype, qv.Q, W, Kp, K, kscale, heads, E, qv.ws,
                                        (hipStream_t)stream),
                     "misa_route_heads launch");
+}
+
+misa_status misa_route_heads_static(const misa_problem* p, const void* Q, const float* W, const float* Kp,
+                                    const void* K, const float* kscale, int32_t* heads, float* E,
+                                    void* stream) {
+  misa::Prob pr;
+  misa_status st = check_problem(p, &pr);
+  if (st != MISA_OK) return st;
+  if ((st = check_queries(Q, W)) != MISA_OK) return st;
+  if ((st = check_keys(p, K, kscale)) != MISA_OK) return st;
+  if (!Kp || !heads) return fail(MISA_ERR_INVALID_ARG, "Kp or heads is NULL");
+  const size_t need = ws_bytes_for(pr, MISA_OP_ROUTE, 0) + q_stage_bytes(p);
+  if (need > (size_t)MISA_ROUTE_STATIC_SCRATCH_BYTES)
+    return fail(MISA_ERR_UNSUPPORTED,
+                "misa_route_heads_static: the problem needs %zu bytes of scratch, the built-in array holds %zu; "
+                "use misa_route_heads with a workspace",
+                need, (size_t)MISA_ROUTE_STATIC_SCRATCH_BYTES);
+  // Address of this device's copy of the array, looked up once per device with that device
+  // current.  The array's name is only a host-side handle: kernels get the looked-up address.
+  static std::atomic<void*> scratch_of_device[64];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_result(e, "hipGetDevice");
+  void* ptr = (dev >= 0 && dev < 64) ? scratch_of_device[dev].load(std::memory_order_acquire) : nullptr;
+  if (!ptr) {
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return hip_result(e != hipSuccess ? e : hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+    if (dev >= 0 && dev < 64) scratch_of_device[dev].store(ptr, std::memory_order_release);
+  }
+  QView qv;
+  if ((st = stage_queries(p, Q, need - q_stage_bytes(p), ptr, (size_t)MISA_ROUTE_STATIC_SCRATCH_BYTES, stream,
+                          &qv)) != MISA_OK)
+    return st;
+  return hip_result(misa::launch_route(pr, p->k_dtype, qv.q_dtype, qv.Q, W, Kp, K, kscale, heads, E, qv.ws,
+                                       (hipStream_t)stream),
+                    "misa_route_heads_static launch");
 }
 
 misa_status misa_route_heads_proxy(const misa_problem* p, const void* Q, const float* W, int32_t kind,

@@ -22,6 +22,9 @@ if not os.path.exists(LIB_PATH):
 lib = ctypes.CDLL(LIB_PATH)
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
+# Whether fp8 queries with fp8 keys are scored on the fp8 matrix instruction by the prefill kernels
+# (otherwise they are widened to bf16 first); bench.py labels its lines with it.
+HAS_FP8_MFMA = False
 DTYPE_CODES = {"f32": F32, "bf16": BF16, "e4m3": FP8_E4M3}
 OP_POOL, OP_ROUTE, OP_SCORE, OP_TOPK, OP_RERANK, OP_SELECT, OP_HISA = range(7)
 STATUS_NAMES = {0: "MISA_OK", 1: "MISA_ERR_INVALID_ARG", 2: "MISA_ERR_UNSUPPORTED",
@@ -48,6 +51,8 @@ lib.misa_pool_keys_update.restype = ctypes.c_int
 lib.misa_pool_keys_update.argtypes = [_P, _V, _V, _V, _V, ctypes.c_int32, _V, ctypes.c_size_t, _V]
 lib.misa_route_heads.restype = ctypes.c_int
 lib.misa_route_heads.argtypes = [_P, _V, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]
+lib.misa_route_heads_static.restype = ctypes.c_int
+lib.misa_route_heads_static.argtypes = [_P, _V, _V, _V, _V, _V, _V, _V, _V]
 lib.misa_route_heads_proxy.restype = ctypes.c_int
 lib.misa_route_heads_proxy.argtypes = [_P, _V, _V, ctypes.c_int32, _V, _V, _V]
 lib.misa_score_tokens.restype = ctypes.c_int
@@ -168,6 +173,15 @@ def route_heads(p: Problem, Q, W, Kp, K, kscale, heads, E=None, ws=None) -> None
     w, wb = _ws(ws)
     _check(lib.misa_route_heads(ctypes.byref(p.c()), _ptr(Q), _ptr(W), _ptr(Kp), _ptr(K), _ptr(kscale),
                                 _ptr(heads), _ptr(E), w, wb, _stream()))
+
+
+ROUTE_STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def route_heads_static(p: Problem, Q, W, Kp, K, kscale, heads, E=None) -> None:
+    """route_heads without a workspace: scratch is an array inside the library (no allocation)."""
+    _check(lib.misa_route_heads_static(ctypes.byref(p.c()), _ptr(Q), _ptr(W), _ptr(Kp), _ptr(K), _ptr(kscale),
+                                       _ptr(heads), _ptr(E), _stream()))
 
 
 ROUTER_BLOCK_POOLED, ROUTER_GATE, ROUTER_QUERY_NORM = range(3)

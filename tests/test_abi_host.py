@@ -134,3 +134,14 @@ def test_paginate_places_every_key_where_the_page_table_says(misa):
             row = int(table[i, s // P]) * P + s % P
             assert torch.equal(pool.view(-1, 128)[row], K[i, s])
             assert spool.view(-1)[row] == ks[i, s]
+
+
+def test_route_heads_static_rejects_problems_beyond_its_scratch_array(misa):
+    # 300 decode sequences need 300 x 64 x 64 floats of partial sums: more than the 4 MiB array
+    p = _prob(misa, n_seq=300)
+    assert misa.workspace_bytes(p, misa.OP_ROUTE) > misa.ROUTE_STATIC_SCRATCH_BYTES
+    st = misa.lib.misa_route_heads_static(ctypes.byref(p.c()), FAKE, FAKE, FAKE, FAKE, None, FAKE, None, None)
+    assert st == 2 and b"scratch" in misa.lib.misa_last_error()
+    # argument validation comes first, as in misa_route_heads
+    assert misa.lib.misa_route_heads_static(ctypes.byref(_prob(misa).c()), None, FAKE, FAKE, FAKE, None, FAKE,
+                                            None, None) == 1

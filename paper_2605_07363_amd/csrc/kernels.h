@@ -3,6 +3,7 @@
 #pragma once
 
 #include <algorithm>
+#include <atomic>
 
 #include "common.h"
 
@@ -74,16 +75,22 @@ hipError_t launch_hisa(const Prob& p, int k_dtype, int q_dtype, const void* Q, c
                        int* idx, float* val, void* ws, hipStream_t st);
 
 // Raises a kernel's dynamic-LDS limit when a launch needs more than any launch before it on the
-// current device (`seen` is the caller's per-kernel record, one entry per device; devices past
-// the 64th get the attribute set on every launch).
-inline hipError_t ensure_dynamic_lds(const void* func, size_t lds, size_t (&seen)[64]) {
+// current device.  `seen` is the caller's per-kernel record, one entry per device (the only state
+// the library keeps besides its error text: atomics, so host threads may call concurrently; a
+// lost update only repeats the cheap attribute call).  Devices past the 64th get the attribute
+// set on every launch.
+using LdsSeen = std::atomic<size_t>[64];
+inline hipError_t ensure_dynamic_lds(const void* func, size_t lds, LdsSeen& seen) {
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   const bool tracked = dev >= 0 && dev < 64;
-  if (tracked && lds <= seen[dev]) return hipSuccess;
+  if (tracked && lds <= seen[dev].load(std::memory_order_acquire)) return hipSuccess;
   e = hipFuncSetAttribute(func, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e == hipSuccess && tracked) seen[dev] = lds;
+  if (e == hipSuccess && tracked) {
+    size_t cur = seen[dev].load(std::memory_order_relaxed);
+    while (cur < lds && !seen[dev].compare_exchange_weak(cur, lds, std::memory_order_release)) {}
+  }
   return e;
 }
 

@@ -434,7 +434,7 @@ hipError_t launch_select(const Prob& p, int k_dtype, int q_dtype, const void* Q,
   const size_t lds = select_lds_bytes(p);  // at most 128 KB (L <= 524288)
 #define GO(NT, EPT)                                                                                 \
   do {                                                                                              \
-    static size_t seen[64] = {};                                                                    \
+    static LdsSeen seen;                                                                            \
     e = ensure_dynamic_lds(reinterpret_cast<const void*>(select_rows_kernel<NT, EPT>), lds, seen);  \
     if (e != hipSuccess) return e;                                                                  \
     select_rows_kernel<NT, EPT><<<rows, NT, lds, st>>>(p, cand, count, tau, upper, l.cap, k, l.qwg, \

@@ -576,7 +576,7 @@ size_t topk_ws_bytes(const Prob& p, int k) {
 
 template <int WHICH>  // 0: topk_kernel<false>, 1: topk_kernel<true>, 2: topk_only_kernel
 static hipError_t set_lds_limit(size_t lds) {
-  static size_t seen[64] = {};
+  static LdsSeen seen;
   const void* f = WHICH == 0 ? reinterpret_cast<const void*>(topk_kernel<false>)
                 : WHICH == 1 ? reinterpret_cast<const void*>(topk_kernel<true>)
                              : reinterpret_cast<const void*>(topk_only_kernel);
@@ -600,9 +600,9 @@ hipError_t launch_topk(const Prob& p, const float* S, int row_len, int k, const 
     int* pre = static_cast<int*>(ws);
     const int rlen = range_len(p.L);
     const dim3 g2((p.L + rlen - 1) / rlen, p.n_q, p.n_seq);
-    topk_prefilter_kernel<<<g2, kTopkThreads, 0, st>>>(p, S, k, rlen, pre);
-    hipError_t e = set_lds_limit<1>(lds);
+    hipError_t e = set_lds_limit<1>(lds);   // before the first launch: a failure leaves nothing enqueued
     if (e != hipSuccess) return e;
+    topk_prefilter_kernel<<<g2, kTopkThreads, 0, st>>>(p, S, k, rlen, pre);
     topk_kernel<true><<<grid, kTopkThreads, lds, st>>>(p, S, row_len, k, map, idx, val, pre, rlen, false);
     return hipGetLastError();
   }

@@ -22,8 +22,7 @@ import json
 import sys
 
 
-def overlap(a, b):
-    """Mean over rows of |a_row ∩ b_row| / |b_row| for index tensors [rows, k] (entries -1 = none)."""
+def _membership(a, b):
     import torch
     n = int(max(a.max(), b.max())) + 2
     rows = a.shape[0]
@@ -31,9 +30,28 @@ def overlap(a, b):
     mb = torch.zeros_like(ma)
     ma.scatter_(1, (a.long() + 1), True)
     mb.scatter_(1, (b.long() + 1), True)
-    ma[:, 0] = False
+    ma[:, 0] = False          # column 0 collects the -1 entries (no token)
     mb[:, 0] = False
-    return float(((ma & mb).sum(1).float() / mb.sum(1).clamp(min=1).float()).mean())
+    return ma, mb
+
+
+def overlap_stats(a, b):
+    """Per row of two index tensors [rows, ka], [rows, kb] (entries -1 = none): the fraction of
+    b's tokens that a holds as well (recall of b; 1 for an empty b) and the intersection over
+    union of the two sets (Eq. iou; 1 when both are empty).  Returns two float tensors [rows]."""
+    ma, mb = _membership(a, b)
+    inter = (ma & mb).sum(1).double()
+    nb = mb.sum(1).double()
+    union = (ma | mb).sum(1).double()
+    one = inter.new_ones(())
+    recall = (inter / nb.clamp(min=1)).where(nb > 0, one)
+    iou = (inter / union.clamp(min=1)).where(union > 0, one)
+    return recall, iou
+
+
+def overlap(a, b):
+    """Mean over rows of |a_row ∩ b_row| / |b_row| for index tensors [rows, k] (entries -1 = none)."""
+    return float(overlap_stats(a, b)[0].mean())
 
 
 def main() -> int:

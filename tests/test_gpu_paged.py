@@ -6,7 +6,9 @@ from dataclasses import replace
 import numpy as np
 import pytest
 
+from oracle import misa_oracle as O
 from paper_2605_07363_amd import workloads as WL
+from helpers import assert_scores_close, check_index_set, oracle_view
 
 pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
@@ -86,6 +88,42 @@ def test_every_stage_matches_the_contiguous_layout(misa, name, page_size):
     b = run_stages(misa, wl, pg)
     for key in a:
         assert torch.equal(a[key], b[key]), f"{key} differs between the layouts ({name}, pages of {page_size})"
+
+
+@pytest.mark.parametrize("name,page_size", [("fp8_prefill", 64), ("bf16_decode", 16), ("fp8_B1024", 256)])
+def test_paged_stages_against_the_oracle(misa, name, page_size):
+    # the paged layout compared with the oracle itself, stage by stage (ragged lengths), not only
+    # with the contiguous layout
+    wl = CASES[name]
+    rng = np.random.default_rng(11)
+    seq_len = rng.integers(wl.L // 2, wl.L + 1, wl.n_seq).astype(np.int32)
+    inp = WL.make_inputs(wl, seed=7 + sum(map(ord, name)), seq_len=seq_len)
+    pg = misa.paginate(misa.to_device(inp), page_size, seed=3)
+    out = {k: v.cpu().numpy() for k, v in run_stages(misa, wl, pg).items()}
+    k1 = min(wl.k_cand or wl.k, wl.L)
+    k2 = min(wl.k, k1)
+    for s in range(wl.n_seq):
+        for t in range(wl.n_q):
+            K, q, w, n = oracle_view(inp, s, t)
+            what = f"paged {name} {s},{t}"
+            if t == 0:
+                ref_Kp = O.pool_keys(K, wl.B, int(seq_len[s]))
+                assert_scores_close(out["Kp"][s, :ref_Kp.shape[0]], ref_Kp, "pooled keys " + what)
+            _, ref_E = O.route_heads(q, w, K, wl.B, wl.h, n)
+            assert_scores_close(out["E"][s, t], ref_E, "E " + what)
+            check_index_set(out["heads"][s, t], ref_E, wl.h, "heads " + what)
+            ref_S = O.score_tokens(q, w, out["heads"][s, t], K, n)
+            assert_scores_close(out["S"][s, t, :n], ref_S, "scores " + what)
+            assert np.all(np.isneginf(out["S"][s, t, n:]))
+            dense = O.dsa_scores(q, w, K, n)
+            assert_scores_close(out["S_dense"][s, t, :n], dense, "dense scores " + what)
+            check_index_set(out["idx"][s, t], ref_S, k1, "tokens " + what)
+            cand = out["idx"][s, t][out["idx"][s, t] >= 0]
+            final = out["rerank_idx"][s, t][out["rerank_idx"][s, t] >= 0]
+            pos = np.searchsorted(cand, final)
+            padded = np.concatenate([pos, np.full(k2 - pos.shape[0], -1, dtype=pos.dtype)])
+            check_index_set(padded, dense[cand], k2, "re-rank " + what)
+            assert_scores_close(out["rerank_val"][s, t, :final.shape[0]], dense[final], "re-rank values " + what)
 
 
 def test_pool_update_select_and_comparison_indexers(misa):

@@ -25,6 +25,7 @@ def misa():
 
 
 def run_and_check(misa, wl, inp, rows=None, page_size=0):
+    """rows: the (sequence, query) rows compared with the oracle (default: all)."""
     dv = misa.to_device(inp)
     if page_size:
         dv = misa.paginate(dv, page_size, seed=page_size)
@@ -111,7 +112,7 @@ def _sample_rows(wl, count, seed=3):
     return [rows[i] for i in sorted(pick)]
 
 
-@pytest.mark.parametrize("name,count", [("c1", 10), ("c3", 4), ("c2", 6), ("c4", 4)])
+@pytest.mark.parametrize("name,count", [("c1", 12), ("c3", 6), ("c2", 32), ("c4", 32)])
 def test_full_size_sampled_rows(misa, name, count):
     wl = WL.WORKLOADS[name]
     run_and_check(misa, wl, WL.make_inputs(wl), _sample_rows(wl, count))

@@ -106,6 +106,12 @@ def test_pool_keys_update_after_append(misa, name):
     stale = Kp.clone()
     misa.pool_keys_update(p_new, dv["K"], dv["kscale"], Kp, old_dev, 5, ws)
     assert torch.equal(Kp, full)
+    got = Kp.cpu().numpy()
+    for s in range(wl.n_seq):                           # the updated pooled keys are the block means of Eq. pool
+        K, _, _, n = oracle_view(inp, s, 0)
+        ref = O.pool_keys(K, wl.B, n)
+        assert_scores_close(got[s, :ref.shape[0]], ref, f"updated pool {name} seq {s}")
+        assert not got[s, ref.shape[0]:].any()
     for s in range(wl.n_seq):                           # blocks before the first changed one were not written
         first = int(old_len[s]) // wl.B
         assert torch.equal(Kp[s, :first], stale[s, :first])
@@ -544,7 +550,8 @@ def test_pool_update_random(misa, seed):
                    k_dtype=["f32", "bf16", "e4m3"][seed % 3], name=f"pu{seed}")
     new_len = rng.integers(0, L + 1, wl.n_seq).astype(np.int32)
     old_len = (new_len - rng.integers(0, 3 * B + 2, wl.n_seq)).clip(0).astype(np.int32)
-    dv = misa.to_device(WL.make_inputs(wl, seed=seed, seq_len=new_len))
+    inp = WL.make_inputs(wl, seed=seed, seq_len=new_len)
+    dv = misa.to_device(inp)
     if seed % 3 == 1:
         dv = misa.paginate(dv, 64, seed=seed)
     p_new = dv["problem"]
@@ -556,6 +563,14 @@ def test_pool_update_random(misa, seed):
     misa.pool_keys(replace(p_new, seq_len=old_dev), dv["K"], dv["kscale"], Kp, ws)
     misa.pool_keys_update(p_new, dv["K"], dv["kscale"], Kp, old_dev, p_new.M, ws)
     assert torch.equal(Kp, full)
+    # directly against the block means of Eq. pool (sliced blocks, ragged lengths, paged keys included);
+    # entries past a sequence's last block keep what the pooling at the old length left (zeros)
+    got = Kp.cpu().numpy()
+    for s in range(wl.n_seq):
+        K, _, _, n = oracle_view(inp, s, 0)
+        ref = O.pool_keys(K, B, n)
+        assert_scores_close(got[s, :ref.shape[0]], ref, f"pool update pu{seed} seq {s}")
+        assert not got[s, ref.shape[0]:].any()
 
 
 @pytest.mark.parametrize("seed", range(9))

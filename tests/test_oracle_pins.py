@@ -463,3 +463,42 @@ def test_hisa_reductions_and_invariants():
         np.testing.assert_array_equal(bs["blocks"], r["blocks"])
         np.testing.assert_array_equal(bs["tokens"], omega)
     assert O.hisa(q, w, K, B, 3, k, 0)["tokens"].shape == (0,)
+
+
+def test_recall_and_iou_hand_values_on_sets_of_different_size():
+    # Eq. iou and the recall of a reference set, worked by hand; the two sets differ in size so
+    # that dividing by the wrong set's size (or by the union instead of the reference) fails.
+    sel, ref = [1, 2, 3, 4, 5, 6], [4, 5, 6, 7]
+    assert O.recall(sel, ref) == 3 / 4          # 4, 5, 6 of the four reference tokens
+    assert O.recall(ref, sel) == 3 / 6
+    assert O.iou(sel, ref) == 3 / 7             # union {1..7}
+    assert O.iou(ref, sel) == 3 / 7
+    assert O.recall([9], [1, 2, 3]) == 0.0 and O.iou([9], [1, 2, 3]) == 0.0
+    assert O.recall([1, 2, 3], [2]) == 1.0 and O.iou([1, 2, 3], [2]) == 1 / 3
+    assert O.recall([], []) == 1.0 and O.iou([], []) == 1.0
+    assert O.recall([], [5]) == 0.0
+
+
+def test_overlap_statistics_of_the_report_generator_match_the_oracle_row_by_row():
+    # recall / IoU as bench.py and the recall sweep compute them (torch, index rows padded with -1)
+    torch = pytest.importorskip("torch")
+    from paper_2605_07363_amd.recall_sweep import overlap, overlap_stats
+    rng = np.random.default_rng(44)
+    rows, ka, kb, n = 40, 24, 16, 60
+    a = np.full((rows, ka), -1, dtype=np.int32)
+    b = np.full((rows, kb), -1, dtype=np.int32)
+    for r in range(rows):
+        na, nb = int(rng.integers(0, ka + 1)), int(rng.integers(0, kb + 1))
+        if r == 0:
+            na, nb = 0, 0
+        if r == 1:
+            na, nb = ka, 0
+        a[r, :na] = np.sort(rng.choice(n, na, replace=False))
+        b[r, :nb] = np.sort(rng.choice(n, nb, replace=False))
+    rec, iou = overlap_stats(torch.from_numpy(a), torch.from_numpy(b))
+    for r in range(rows):
+        sa, sb = a[r][a[r] >= 0], b[r][b[r] >= 0]
+        assert rec[r].item() == pytest.approx(O.recall(sa, sb), abs=1e-12), r
+        assert iou[r].item() == pytest.approx(O.iou(sa, sb), abs=1e-12), r
+    assert overlap(torch.from_numpy(a), torch.from_numpy(b)) == pytest.approx(
+        np.mean([O.recall(a[r][a[r] >= 0], b[r][b[r] >= 0]) for r in range(rows)]), abs=1e-12)

@@ -110,6 +110,27 @@ union Frag {
   uint32_t w[4];
 };
 
+// Buffer descriptors (raw, unstrided): accesses at byte offsets >= num_bytes read zeros and
+// drop stores.  Addresses are descriptor base + per-lane byte offset + wave-uniform byte offset.
+using BufferRsrc = __amdgpu_buffer_rsrc_t;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+// base and num_bytes must be the same in every lane: they are moved to scalar registers here,
+// so that the compiler keeps the descriptor there instead of looping over "distinct" lanes.
+__device__ __forceinline__ BufferRsrc make_rsrc(const void* base, uint32_t num_bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+  void* uniform = reinterpret_cast<void*>(((uint64_t)hi << 32) | lo);
+  return __builtin_amdgcn_make_buffer_rsrc(uniform, 0, (int)__builtin_amdgcn_readfirstlane(num_bytes), 0x00020000);
+}
+__device__ __forceinline__ uint4 buffer_load16(BufferRsrc r, uint32_t lane_off, uint32_t wave_off = 0) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)wave_off, 0);
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void buffer_store4(BufferRsrc r, uint32_t lane_off, uint32_t wave_off, float x) {
+  __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(x), r, (int)lane_off, (int)wave_off, 0);
+}
+
 // NT = 16-row head tiles (heads <= 16 * NT); a wavefront takes STEPS pipeline
 // steps of G 64-key groups each.
 template <int KDT, int NT, int STEPS, int G, bool PAGED>
@@ -407,6 +428,13 @@ __device__ __forceinline__ void score_tile_body(
   constexpr int CPR = ROW_BYTES / 16;  // chunks per key row
   uint4 st0 = make_uint4(0, 0, 0, 0), st1 = st0, st2 = st0, st3 = st0;
   float st_scale = 1.f;
+  // A contiguous, unsampled cache is read through a buffer descriptor of the sequence's keys:
+  // a tile is one linear piece (thread tid takes bytes 16 tid + 4096 i of it), so a thread's
+  // offsets only advance by the tile size, and rows past the end of the cache read as zeros
+  // (the descriptor's range check) instead of being clamped per lane.
+  constexpr bool LINEAR = !SAMPLE && !PAGED;
+  const BufferRsrc krsrc = make_rsrc(kbase, (uint32_t)p.L * (uint32_t)ROW_BYTES);
+  uint32_t koff = (uint32_t)k_begin * ROW_BYTES + (uint32_t)tid * 16u;  // next tile to request
   // Cache row of key j of tile space (clamped into the cache).  Sampling takes key
   // 16 j + (top four bits of a multiplicative hash of j) of every group of 16.
   // With a page table the row is the one in the page pool and kbase the pool itself.
@@ -415,37 +443,51 @@ __device__ __forceinline__ void score_tile_body(
     if (SAMPLE) j = j * kSampleStride + (int)(((uint32_t)j * 2654435761u) >> 28);
     return PAGED ? key_slot<true>(p, seq, j) : (size_t)j;
   };
+  // Requests the tile that starts at key k0; successive calls ask for successive tiles.
 #define MISA_TILE_LOAD(k0)                                                                        \
   do {                                                                                            \
-    st0 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + tid / CPR) * ROW_BYTES + (tid % CPR) * 16); \
-    st1 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 256) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
-    if (NLD == 4) {                                                                               \
-      st2 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 512) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
-      st3 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 768) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
+    if (LINEAR) {                                                                                 \
+      st0 = buffer_load16(krsrc, koff);                                                           \
+      st1 = buffer_load16(krsrc, koff + 4096u);                                                   \
+      if (NLD == 4) {                                                                             \
+        st2 = buffer_load16(krsrc, koff + 8192u);                                                 \
+        st3 = buffer_load16(krsrc, koff + 12288u);                                                \
+      }                                                                                           \
+      koff += kKT * ROW_BYTES;                                                                    \
+    } else {                                                                                      \
+      st0 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + tid / CPR) * ROW_BYTES + (tid % CPR) * 16); \
+      st1 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 256) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
+      if (NLD == 4) {                                                                             \
+        st2 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 512) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
+        st3 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 768) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
+      }                                                                                           \
     }                                                                                             \
     if (KDT == MISA_FP8_E4M3 && tid < kKT) st_scale = kscale[(PAGED ? (size_t)0 : (size_t)seq * p.L) + key_row((k0) + tid)]; \
   } while (0)
-  auto put_chunk = [&](int b, int chunk, const uint4& v) {  // registers -> LDS, bf16, padded rows
-    const int row = chunk / CPR, c = chunk % CPR;
+  // registers -> LDS (bf16, padded rows): chunk tid + 256 i is chunk tid % CPR of row
+  // tid / CPR + (256 / CPR) i, so the four writes differ by a constant
+  uint4* const lds_put = &ktile[0][0] + (tid / CPR) * kKP + (KDT == MISA_BF16 ? tid % CPR : 2 * (tid % CPR));
+  auto put_chunk = [&](int b, int i, const uint4& v) {
+    uint4* dst = lds_put + b * (kKT * kKP) + i * ((256 / CPR) * kKP);
     if (KDT == MISA_BF16) {
-      ktile[b][row * kKP + c] = v;
+      dst[0] = v;
     } else {
       uint4 lo, hi;
       fp8x4_to_bf16x4(v.x, lo.x, lo.y);
       fp8x4_to_bf16x4(v.y, lo.z, lo.w);
       fp8x4_to_bf16x4(v.z, hi.x, hi.y);
       fp8x4_to_bf16x4(v.w, hi.z, hi.w);
-      ktile[b][row * kKP + 2 * c] = lo;
-      ktile[b][row * kKP + 2 * c + 1] = hi;
+      dst[0] = lo;
+      dst[1] = hi;
     }
   };
 #define MISA_TILE_STORE(b)                                        \
   do {                                                            \
-    put_chunk((b), tid, st0);                                     \
-    put_chunk((b), tid + 256, st1);                               \
+    put_chunk((b), 0, st0);                                       \
+    put_chunk((b), 1, st1);                                       \
     if (NLD == 4) {                                               \
-      put_chunk((b), tid + 512, st2);                             \
-      put_chunk((b), tid + 768, st3);                             \
+      put_chunk((b), 2, st2);                                     \
+      put_chunk((b), 3, st3);                                     \
     }                                                             \
     if (KDT == MISA_FP8_E4M3 && tid < kKT) kscl[(b)][tid] = st_scale; \
   } while (0)
@@ -454,6 +496,9 @@ __device__ __forceinline__ void score_tile_body(
   // rows relative to the first row of the tile (uniform base + lane offset stores)
   constexpr int NQL = HS == 8 ? RT * 2 : (HS == 16 ? RT : 1);  // queries per lane
   float* s_tile = S + ((size_t)seq * p.n_q + q_base) * LT;
+  // Unmasked tiles store through a descriptor of the workgroup's score rows: the address of a
+  // store is a per-lane constant (row, column inside the tile) plus the wave-uniform tile start.
+  const BufferRsrc srsrc = make_rsrc(s_tile, (uint32_t)QWG * (uint32_t)LT * 4u);
   int qn[NQL];
   uint32_t qoff[NQL];
   // filter mode: thresholds of this lane's queries and the lengths of the wavefront's
@@ -538,6 +583,7 @@ __device__ __forceinline__ void score_tile_body(
   };
   auto finish = [&](auto plain_tag, float (&out)[NQL], int key, float scale) {
     constexpr bool PLAIN = decltype(plain_tag)::value;
+    const int key0 = __builtin_amdgcn_readfirstlane(key - col);   // first key of the column tile
     if (KDT == MISA_FP8_E4M3) {
 #pragma unroll
       for (int j = 0; j < NQL; ++j) out[j] *= scale;
@@ -556,7 +602,7 @@ __device__ __forceinline__ void score_tile_body(
       }
     } else if (PLAIN) {
 #pragma unroll
-      for (int j = 0; j < NQL; ++j) s_tile[qoff[j] + (uint32_t)key] = out[j];
+      for (int j = 0; j < NQL; ++j) buffer_store4(srsrc, (qoff[j] + (uint32_t)col) * 4u, (uint32_t)key0 * 4u, out[j]);
     } else {
 #pragma unroll
       for (int j = 0; j < NQL; ++j)
@@ -677,57 +723,80 @@ __device__ __forceinline__ void score_tile_body(
   // LDS tile: [tile i, columns 32..63 | epilogue of columns 0..31], stage tile
   // i+1 into the other LDS buffer, barrier, [tile i+1, columns 0..31 | epilogue
   // of tile i, columns 32..63].
+  // Per iteration j, in one straight line: request tile j + 2, [tile j+1, columns 0..31 |
+  // epilogue of tile j, columns 32..63], [tile j+1, columns 32..63 | epilogue of tile j+1,
+  // columns 0..31], stage tile j + 2 into the LDS buffer tile j has left, barrier.  Requests
+  // and staging are unconditional (tiles past the range read zeros or clamped rows into a
+  // buffer nobody reads), so an iteration has no branch between a request and its use and
+  // every wait counts exactly the score stores issued in between.
   const int n_tiles = k_begin < k_stop ? (k_stop - k_begin + kKT - 1) / kKT : 0;
   if (n_tiles > 0) {
     MISA_TILE_LOAD(k_begin);
-    MISA_TILE_STORE(0);
+    {   // the second tile is requested before the first is staged (the registers are still free)
+      const uint4 f0 = st0, f1 = st1, f2 = st2, f3 = st3;
+      const float fs = st_scale;
+      MISA_TILE_LOAD(k_begin + kKT);
+      put_chunk(0, 0, f0);
+      put_chunk(0, 1, f1);
+      if (NLD == 4) {
+        put_chunk(0, 2, f2);
+        put_chunk(0, 3, f3);
+      }
+      if (KDT == MISA_FP8_E4M3 && tid < kKT) kscl[0][tid] = fs;
+    }
+    MISA_TILE_STORE(1);
     // Every load of the prologue (query operand, gates) has landed before the loop
     // starts, so the waits inside the loop only concern loads issued inside it.
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    if (n_tiles > 1) MISA_TILE_LOAD(k_begin + kKT);
     f32x16 accA[RT], accB[RT];
     float scaleA = 1.f, scaleB = 1.f;
     mfma_tile(accA, 0);
     if (KDT == MISA_FP8_E4M3) scaleA = kscl[0][col];
-    auto body = [&](auto tag, int i) {
-      const int buf = i & 1, k0 = k_begin + i * kKT;
-      const bool more = i + 1 < n_tiles;
-      if (FILTER) filter_step(tag, accB, (buf * 64 + 32) * kKP, accA, k0 + col, scaleA);
-      else tile_step(tag, accB, (buf * 64 + 32) * kKP, accA, k0 + col, scaleA);
-      if (KDT == MISA_FP8_E4M3) scaleB = kscl[buf][32 + col];
-      if (more) MISA_TILE_STORE(buf ^ 1);
-      __syncthreads();
-      if (more) {
-        if (i + 2 < n_tiles) MISA_TILE_LOAD(k0 + 2 * kKT);
-        if (FILTER) filter_step(tag, accA, (buf ^ 1) * 64 * kKP, accB, k0 + 32 + col, scaleB);
-        else tile_step(tag, accA, (buf ^ 1) * 64 * kKP, accB, k0 + 32 + col, scaleB);
-        if (KDT == MISA_FP8_E4M3) scaleA = kscl[buf ^ 1][col];
-      } else {
-        if (FILTER) {
-          // the last column tile is finished at once: its entries (up to kKT per list) come
-          // on top of the two steps' worth the body has appended already
-          drain_pending();
-#pragma unroll
-          for (int j = 0; j < NQL; ++j)
-            if (cnt[j] > kStageCap - kKT) flush_list(j);
-        }
-        epilogue(tag, accB, k0 + 32 + col, scaleB);
-      }
-      if (FILTER) {
-#pragma unroll
-        for (int j = 0; j < NQL; ++j)     // up to 2 kKT entries per list and key tile
-          if (cnt[j] > kStageCap - 2 * kKT) flush_list(j);
-      }
-    };
     // leading tiles that need no masks, then the rest
     const int n_plain = min(n_tiles, max(0, (plain_end - k_begin) / kKT));
-    for (int i = 0; i < n_plain; ++i) body(Yes{}, i);
-    for (int i = n_plain; i < n_tiles; ++i) body(No{}, i);
-    if (FILTER) {  // (the last body has drained the pending sums)
+    auto half = [&](auto tag) {   // tile 0, columns 32..63 | epilogue of its columns 0..31
+      if (FILTER) filter_step(tag, accB, 32 * kKP, accA, k_begin + col, scaleA);
+      else tile_step(tag, accB, 32 * kKP, accA, k_begin + col, scaleA);
+      if (KDT == MISA_FP8_E4M3) scaleB = kscl[0][32 + col];
+    };
+    if (n_plain > 0) half(Yes{});
+    else half(No{});
+    auto body = [&](auto tag, int j) {
+      const int nb = (j + 1) & 1, k0 = k_begin + j * kKT;
+      MISA_TILE_LOAD(k0 + 2 * kKT);
+      if (FILTER) filter_step(tag, accA, nb * 64 * kKP, accB, k0 + 32 + col, scaleB);
+      else tile_step(tag, accA, nb * 64 * kKP, accB, k0 + 32 + col, scaleB);
+      if (KDT == MISA_FP8_E4M3) scaleA = kscl[nb][col];
+      if (FILTER) filter_step(tag, accB, (nb * 64 + 32) * kKP, accA, k0 + kKT + col, scaleA);
+      else tile_step(tag, accB, (nb * 64 + 32) * kKP, accA, k0 + kKT + col, scaleA);
+      if (KDT == MISA_FP8_E4M3) scaleB = kscl[nb][32 + col];
+      if (FILTER) {
 #pragma unroll
-      for (int j = 0; j < NQL; ++j)
-        if (cnt[j] > 0) flush_list(j);
+        for (int q = 0; q < NQL; ++q)     // up to 2 kKT entries per list and iteration
+          if (cnt[q] > kStageCap - 2 * kKT) flush_list(q);
+      }
+      MISA_TILE_STORE(nb ^ 1);
+      __syncthreads();
+    };
+    // iteration j finishes columns of the tiles j and j + 1: unmasked when both are
+    for (int j = 0; j < n_plain - 1; ++j) body(Yes{}, j);
+    for (int j = max(n_plain - 1, 0); j < n_tiles - 1; ++j) body(No{}, j);
+    if (FILTER) {
+      // the last column tile is finished at once: its entries (up to kKT per list) come
+      // on top of what the steps have appended already
+      drain_pending();
+#pragma unroll
+      for (int q = 0; q < NQL; ++q)
+        if (cnt[q] > kStageCap - kKT) flush_list(q);
+    }
+    const int k_last = k_begin + (n_tiles - 1) * kKT + 32 + col;
+    if (n_plain == n_tiles) epilogue(Yes{}, accB, k_last, scaleB);
+    else epilogue(No{}, accB, k_last, scaleB);
+    if (FILTER) {
+#pragma unroll
+      for (int q = 0; q < NQL; ++q)
+        if (cnt[q] > 0) flush_list(q);
     }
   }
 #undef MISA_TILE_LOAD

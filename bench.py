@@ -115,13 +115,16 @@ def measure(args, name: str, fused: bool, main_line: bool) -> dict:
         dv = misa.paginate(dv, args.paged, seed=1)
     p = dv["problem"]
     Q, W = dv["Q"], dv["W"]
+    # fp8 queries: a step widens them to bf16 once; prefill workloads with fp8 keys score on the
+    # codes themselves (fp8 matrix instruction), routing and re-ranking use the widened copy
     native_fp8 = bool(args.fp8_queries) and wl.k_dtype == "e4m3" and not wl.decode and misa.HAS_FP8_MFMA
     Q8, p8 = None, None
-    widen = args.fp8_queries and not native_fp8
+    widen = bool(args.fp8_queries)
     if widen:
-        Q8, p8 = Q, p
+        Q8, p8 = Q, (replace(p, q_dtype=misa.FP8_E4M3_MATRIX) if native_fp8 else p)
         Q = torch.empty(Q8.shape, dtype=torch.bfloat16, device="cuda")
         p = replace(p, q_dtype=misa.BF16)
+    Qs = Q8 if native_fp8 else Q
     # Decode caches are far larger than the 256 MB last-level cache; rotating
     # copies keeps every step's key reads cold.  Prefill caches are small and
     # are re-read by every query tile, so one copy is the workload.
@@ -129,6 +132,8 @@ def measure(args, name: str, fused: bool, main_line: bool) -> dict:
     Ks = [dv["K"]] + [dv["K"].clone() for _ in range(n_rot - 1)]
     scales = [dv["kscale"]] + [None if dv["kscale"] is None else dv["kscale"].clone() for _ in range(n_rot - 1)]
     ix = misa.Indexer(p, wl.k, wl.k_cand, fused=fused)
+    if native_fp8:
+        ix.p_score = p8
     incremental = args.incremental_pool and main_line
     newest = torch.full((wl.n_seq,), wl.L - 1, dtype=torch.int32, device="cuda")
     if incremental:
@@ -140,7 +145,7 @@ def measure(args, name: str, fused: bool, main_line: bool) -> dict:
 
     def step(i, ev=None):
         K, ks = Ks[i % n_rot], scales[i % n_rot]
-        mid = [lambda: ix.select_fused(Q, W, K, ks)] if fused else [lambda: ix.score(Q, W, K, ks), ix.select]
+        mid = [lambda: ix.select_fused(Qs, W, K, ks)] if fused else [lambda: ix.score(Qs, W, K, ks), ix.select]
         pool = (lambda: ix.pool_update(K, ks, newest, 1)) if incremental else (lambda: ix.pool(K, ks))
         calls = ([lambda: misa.convert_queries(p8, Q8, Q)] if widen else []) + \
             [pool, lambda: ix.route(Q, W, K, ks)] + mid + \

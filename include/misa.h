@@ -82,7 +82,9 @@ typedef enum misa_status {
 typedef enum misa_dtype {
   MISA_F32 = 0,
   MISA_BF16 = 1,
-  MISA_FP8_E4M3 = 2 /* OCP FP8 E4M3 ("e4m3fn": bias 7, max 448, no infinity)            */
+  MISA_FP8_E4M3 = 2, /* OCP FP8 E4M3 ("e4m3fn": bias 7, max 448, no infinity)           */
+  MISA_FP8_E4M3_MATRIX = 3 /* q_dtype only: e4m3 query codes that may be contracted on the
+                              fp8 matrix instruction (see "fp8 queries" below)             */
 } misa_dtype;
 
 typedef enum misa_op {
@@ -339,7 +341,19 @@ misa_status misa_block_sparse_select(const misa_problem* p, const void* Q, const
  * as for bf16 queries, so results equal those of the widened queries bit for bit.  A caller
  * that runs several stages on the same queries widens them once with misa_convert_queries
  * and passes the result with q_dtype = MISA_BF16.
- *   Q       in   [n_seq, n_q, H, d] uint8, 16-byte aligned (p->q_dtype must be MISA_FP8_E4M3)
+ *
+ * q_dtype = MISA_FP8_E4M3_MATRIX is the same input format, with one permission: when the keys
+ * are MISA_FP8_E4M3 too and the problem has at least 8 queries per sequence (the prefill tile
+ * kernel), misa_score_tokens and misa_select_tokens leave queries and keys as codes and
+ * contract them with the fp8 matrix instruction (v_mfma_f32_32x32x64_f8f6f4): half the matrix
+ * time, no widening, half the staged bytes.  The products are still exact, but that
+ * instruction sums its 64 products in a narrower format than fp32: measured on MI355X, a dot
+ * product of 128 terms comes out within 2^-15 of the sum of the absolute products (fp32
+ * accumulation of the widened values: 2^-22).  Scores therefore carry an absolute error of up
+ * to about 4e-5 of the largest score magnitudes of their row instead of 1e-5, and selections
+ * may differ from the exact ones among scores that close.  All other calls (routing,
+ * re-ranking, decode-shaped problems, other key types) treat it exactly as MISA_FP8_E4M3.
+ *   Q       in   [n_seq, n_q, H, d] uint8, 16-byte aligned (p->q_dtype must be an fp8 type)
  *   Q_bf16  out  [n_seq, n_q, H, d] bf16, 16-byte aligned
  */
 misa_status misa_convert_queries(const misa_problem* p, const void* Q, void* Q_bf16, void* stream);

@@ -37,7 +37,7 @@ misa_status check_problem(const misa_problem* p, misa::Prob* out) {
     return fail(MISA_ERR_INVALID_ARG, "h must be in 1..H (h=%d, H=%d)", p->h, p->H);
   if (p->k_dtype < MISA_F32 || p->k_dtype > MISA_FP8_E4M3)
     return fail(MISA_ERR_INVALID_ARG, "unknown k_dtype %d", p->k_dtype);
-  if (p->q_dtype < MISA_F32 || p->q_dtype > MISA_FP8_E4M3)
+  if (p->q_dtype < MISA_F32 || p->q_dtype > MISA_FP8_E4M3_MATRIX)
     return fail(MISA_ERR_INVALID_ARG, "unknown q_dtype %d", p->q_dtype);
   if (p->n_q > 1 && !p->q_pos)
     return fail(MISA_ERR_INVALID_ARG, "q_pos is required when n_q > 1");
@@ -99,16 +99,33 @@ misa_status hip_result(hipError_t e, const char* what) {
 // see bf16 queries and the rest of the workspace.
 struct QView { const void* Q; int q_dtype; void* ws; size_t ws_bytes; };
 
+bool fp8_queries(const misa_problem* p) {
+  return p->q_dtype == MISA_FP8_E4M3 || p->q_dtype == MISA_FP8_E4M3_MATRIX;
+}
+
+// Scoring calls keep fp8 query codes as they are (fp8 matrix instruction) when the caller allowed
+// it, the keys are fp8 as well and the problem runs on the prefill tile kernel.
+bool native_fp8(const misa_problem* p, const misa::Prob& pr) {
+  return p->q_dtype == MISA_FP8_E4M3_MATRIX && p->k_dtype == MISA_FP8_E4M3 &&
+         misa::tile_path(pr, MISA_FP8_E4M3, MISA_FP8_E4M3);
+}
+
 size_t q_stage_bytes(const misa_problem* p) {
-  if (p->q_dtype != MISA_FP8_E4M3) return 0;
+  if (!fp8_queries(p)) return 0;
   const size_t b = (size_t)p->n_seq * p->n_q * p->H * misa::kD * 2;
   return (b + 255) & ~(size_t)255;
 }
 
-int eff_q_dtype(const misa_problem* p) { return p->q_dtype == MISA_FP8_E4M3 ? MISA_BF16 : p->q_dtype; }
+int eff_q_dtype(const misa_problem* p) { return fp8_queries(p) ? MISA_BF16 : p->q_dtype; }
 
 misa_status stage_queries(const misa_problem* p, const void* Q, size_t need_rest, void* ws,
-                          size_t ws_bytes, void* stream, QView* v) {
+                          size_t ws_bytes, void* stream, QView* v, bool keep_fp8 = false) {
+  if (keep_fp8) {   // the codes go to the kernels as they are; the whole workspace is theirs
+    misa_status st = check_ws(need_rest, ws, ws_bytes);
+    if (st != MISA_OK) return st;
+    v->Q = Q; v->q_dtype = MISA_FP8_E4M3; v->ws = ws; v->ws_bytes = ws_bytes;
+    return MISA_OK;
+  }
   const size_t qb = q_stage_bytes(p);
   misa_status st = check_ws(need_rest + qb, ws, ws_bytes);
   if (st != MISA_OK) return st;
@@ -241,7 +258,8 @@ misa_status misa_route_heads_proxy(const misa_problem* p, const void* Q, const f
   if (!heads) return fail(MISA_ERR_INVALID_ARG, "heads is NULL");
   if (kind != MISA_ROUTER_GATE && kind != MISA_ROUTER_QUERY_NORM)
     return fail(MISA_ERR_INVALID_ARG, "kind must be MISA_ROUTER_GATE or MISA_ROUTER_QUERY_NORM (got %d)", kind);
-  return hip_result(misa::launch_route_proxy(pr, p->q_dtype, kind, Q, W, heads, E, (hipStream_t)stream),
+  const int qd = fp8_queries(p) ? (int)MISA_FP8_E4M3 : p->q_dtype;
+  return hip_result(misa::launch_route_proxy(pr, qd, kind, Q, W, heads, E, (hipStream_t)stream),
                     "misa_route_heads_proxy launch");
 }
 
@@ -255,7 +273,7 @@ misa_status misa_score_tokens(const misa_problem* p, const void* Q, const float*
   if ((st = check_keys(p, K, kscale)) != MISA_OK) return st;
   if (!S) return fail(MISA_ERR_INVALID_ARG, "S is NULL");
   QView qv;
-  if ((st = stage_queries(p, Q, 0, ws, ws_bytes, stream, &qv)) != MISA_OK) return st;
+  if ((st = stage_queries(p, Q, 0, ws, ws_bytes, stream, &qv, native_fp8(p, pr))) != MISA_OK) return st;
   return hip_result(misa::launch_score(pr, p->k_dtype, qv.q_dtype, qv.Q, W, heads, K, kscale, nullptr, 0,
                                        S, (hipStream_t)stream),
                     "misa_score_tokens launch");
@@ -286,8 +304,9 @@ misa_status misa_select_tokens(const misa_problem* p, const void* Q, const float
   if (k < 1) return fail(MISA_ERR_INVALID_ARG, "k must be >= 1 (got %d)", k);
   if (k > misa::kMaxTopK) return fail(MISA_ERR_UNSUPPORTED, "k must be <= 16384 (got %d)", k);
   QView qv;
-  if ((st = stage_queries(p, Q, ws_bytes_for(pr, MISA_OP_SELECT, k, p->k_dtype, eff_q_dtype(p)), ws, ws_bytes,
-                          stream, &qv)) != MISA_OK)
+  const bool native = native_fp8(p, pr);
+  if ((st = stage_queries(p, Q, ws_bytes_for(pr, MISA_OP_SELECT, k, p->k_dtype, native ? (int)MISA_FP8_E4M3 : eff_q_dtype(p)),
+                          ws, ws_bytes, stream, &qv, native)) != MISA_OK)
     return st;
   return hip_result(misa::launch_select(pr, p->k_dtype, qv.q_dtype, qv.Q, W, heads, K, kscale, k, idx, val,
                                         qv.ws, (hipStream_t)stream),
@@ -297,8 +316,9 @@ misa_status misa_select_tokens(const misa_problem* p, const void* Q, const float
 int64_t misa_select_row_flags_offset(const misa_problem* p, int32_t routed, int32_t k) {
   misa::Prob pr;
   if (check_problem(p, &pr) != MISA_OK) return -1;
-  const long long off = misa::select_row_flags_offset(pr, p->k_dtype, eff_q_dtype(p), routed != 0, k);
-  return off < 0 ? off : off + (long long)q_stage_bytes(p);
+  const bool native = native_fp8(p, pr);
+  const long long off = misa::select_row_flags_offset(pr, p->k_dtype, native ? (int)MISA_FP8_E4M3 : eff_q_dtype(p), routed != 0, k);
+  return off < 0 || native ? off : off + (long long)q_stage_bytes(p);
 }
 
 namespace {
@@ -372,7 +392,7 @@ misa_status misa_convert_queries(const misa_problem* p, const void* Q, void* Q_b
   misa::Prob pr;
   misa_status st = check_problem(p, &pr);
   if (st != MISA_OK) return st;
-  if (p->q_dtype != MISA_FP8_E4M3) return fail(MISA_ERR_INVALID_ARG, "q_dtype must be MISA_FP8_E4M3");
+  if (!fp8_queries(p)) return fail(MISA_ERR_INVALID_ARG, "q_dtype must be MISA_FP8_E4M3 or MISA_FP8_E4M3_MATRIX");
   if (!Q || !Q_bf16) return fail(MISA_ERR_INVALID_ARG, "Q or Q_bf16 is NULL");
   if (!aligned(Q, 16) || !aligned(Q_bf16, 16))
     return fail(MISA_ERR_INVALID_ARG, "Q and Q_bf16 must be 16-byte aligned");

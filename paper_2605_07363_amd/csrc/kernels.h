@@ -42,9 +42,10 @@ struct TileAux {
 };
 bool tile_path(const Prob& p, int k_dtype, int q_dtype);  // launch_score uses the tile kernel
 int tile_queries_per_wg(const Prob& p, bool routed);
-hipError_t launch_tile_mode(const Prob& p, int k_dtype, int mode, const TileAux& aux, const void* Q,
-                            const float* W, const int* heads, const void* K, const float* kscale,
-                            float* S, hipStream_t st);
+// q_dtype: MISA_BF16, or MISA_FP8_E4M3 (codes, with fp8 keys only: contracted on the fp8 matrix instruction)
+hipError_t launch_tile_mode(const Prob& p, int k_dtype, int q_dtype, int mode, const TileAux& aux,
+                            const void* Q, const float* W, const int* heads, const void* K,
+                            const float* kscale, float* S, hipStream_t st);
 
 // Fused scoring + top-k (scores are not materialised on the common path).
 size_t select_ws_bytes(const Prob& p, int k_dtype, int q_dtype, int k);

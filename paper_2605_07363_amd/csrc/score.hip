@@ -110,6 +110,12 @@ union Frag {
   uint32_t w[4];
 };
 
+typedef __attribute__((__vector_size__(8 * sizeof(int)))) int i32x8;
+union Frag8 {   // 32 fp8 codes: one operand of the fp8 matrix instruction
+  i32x8 v;
+  uint4 u[2];
+};
+
 // Buffer descriptors (raw, unstrided): accesses at byte offsets >= num_bytes read zeros and
 // drop stores.  Addresses are descriptor base + per-lane byte offset + wave-uniform byte offset.
 using BufferRsrc = __amdgpu_buffer_rsrc_t;
@@ -336,6 +342,7 @@ struct TileGeom {
 
 constexpr int kKT = 64;  // keys per LDS tile
 constexpr int kKP = 17;  // 16-byte slots per key row in LDS: 16 of data + 1 of padding
+constexpr int kKP8 = 9;  // the same for rows kept as fp8 codes: 8 of data + 1 of padding
 // Queries per sequence from which the tiled matrix-core kernel is used.
 constexpr int kTileMinQueries = 8;
 constexpr int kStageCap = 320;  // filter mode: staged candidates per wavefront and pair of queries
@@ -353,7 +360,7 @@ constexpr int kStageCap = 320;  // filter mode: staged candidates per wavefront 
 //   with the half) and moves them to the global lists in batches, one global
 //   atomic per query and batch.
 // The work of one workgroup: query tile q_tile of sequence blockIdx.z, key range blockIdx.x.
-template <int KDT, int HS, int MODE, bool PAGED>
+template <int KDT, int HS, int MODE, bool PAGED, bool Q8>
 __device__ __forceinline__ void score_tile_body(
     const Prob& p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
@@ -364,7 +371,12 @@ __device__ __forceinline__ void score_tile_body(
   constexpr int NQL_ = HS == 8 ? RT * 2 : (HS == 16 ? RT : 1);  // queries per lane
   constexpr int ROW_BYTES = KDT == MISA_BF16 ? 256 : 128;
   constexpr int NLD = KDT == MISA_BF16 ? 4 : 2;  // 16-byte global loads per thread and tile
-  __shared__ uint4 ktile[2][kKT * kKP];
+  // Q8: queries and keys are both e4m3 codes and stay so: the tile holds raw key rows (8 slots +
+  // 1 of padding) and the products run on the fp8 matrix instruction (K = 64 per instruction).
+  static_assert(!Q8 || KDT == MISA_FP8_E4M3, "fp8 queries contract with fp8 keys only");
+  constexpr int KP = Q8 ? kKP8 : kKP;     // 16-byte slots per key row in LDS
+  constexpr int KS = Q8 ? 2 : 8;          // matrix instructions per 32 x 32 output tile
+  __shared__ uint4 ktile[2][kKT * KP];
   __shared__ float kscl[2][kKT];
   __shared__ int nvis[QWG];
   __shared__ int s_head[QWG][HS];
@@ -398,7 +410,8 @@ __device__ __forceinline__ void score_tile_body(
 
   // Stationary operand: row m = col of row tile rt belongs to half-wave (m >> 2) & 1 of the
   // accumulator and to its register r = (m >> 3) * 4 + (m & 3).
-  Frag a[RT][8];
+  Frag a[RT][Q8 ? 1 : 8];
+  Frag8 a8[RT][Q8 ? 2 : 1];   // fp8 operands: k-step ks, half-wave hf: components 64 ks + 32 hf .. + 31
   float gate[RT][16];
   {
     const int m = col, mhf = (m >> 2) & 1, mr = (m >> 3) * 4 + (m & 3);
@@ -406,12 +419,23 @@ __device__ __forceinline__ void score_tile_body(
     for (int rt = 0; rt < RT; ++rt) {
       const int qi = wave * QW + G::query_of(rt, mhf, mr), slot = G::slot_of(rt, mr);
       const int head = s_head[qi][slot];
-      const uint16_t* src =
-          Q + (((size_t)seq * p.n_q + min(q_base + qi, p.n_q - 1)) * p.H + max(head, 0)) * kD + hf * 8;
+      const size_t qhead = (((size_t)seq * p.n_q + min(q_base + qi, p.n_q - 1)) * p.H + max(head, 0)) * kD;
+      if (Q8) {
+        const uint8_t* src = reinterpret_cast<const uint8_t*>(Q) + qhead + hf * 32;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const uint4 v = *reinterpret_cast<const uint4*>(src + ks * 16);
-        a[rt][ks].u = head >= 0 ? v : make_uint4(0, 0, 0, 0);
+        for (int ks = 0; ks < (Q8 ? 2 : 0); ++ks)
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const uint4 v = *reinterpret_cast<const uint4*>(src + ks * 64 + u * 16);
+            a8[rt][ks].u[u] = head >= 0 ? v : make_uint4(0, 0, 0, 0);
+          }
+      } else {
+        const uint16_t* src = Q + qhead + hf * 8;
+#pragma unroll
+        for (int ks = 0; ks < (Q8 ? 0 : 8); ++ks) {
+          const uint4 v = *reinterpret_cast<const uint4*>(src + ks * 16);
+          a[rt][ks].u = head >= 0 ? v : make_uint4(0, 0, 0, 0);
+        }
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -466,10 +490,10 @@ __device__ __forceinline__ void score_tile_body(
   } while (0)
   // registers -> LDS (bf16, padded rows): chunk tid + 256 i is chunk tid % CPR of row
   // tid / CPR + (256 / CPR) i, so the four writes differ by a constant
-  uint4* const lds_put = &ktile[0][0] + (tid / CPR) * kKP + (KDT == MISA_BF16 ? tid % CPR : 2 * (tid % CPR));
+  uint4* const lds_put = &ktile[0][0] + (tid / CPR) * KP + (KDT == MISA_BF16 || Q8 ? tid % CPR : 2 * (tid % CPR));
   auto put_chunk = [&](int b, int i, const uint4& v) {
-    uint4* dst = lds_put + b * (kKT * kKP) + i * ((256 / CPR) * kKP);
-    if (KDT == MISA_BF16) {
+    uint4* dst = lds_put + b * (kKT * KP) + i * ((256 / CPR) * KP);
+    if (KDT == MISA_BF16 || Q8) {
       dst[0] = v;
     } else {
       uint4 lo, hi;
@@ -556,23 +580,41 @@ __device__ __forceinline__ void score_tile_body(
   // LDS fragment position of this lane (16-byte units): row col of column tile 0, chunk
   // 2 ks + hf.  Rows are 17 slots apart, so the 16 lanes that read together hit 16 different
   // bank groups, and the k-step only adds a constant: one address register per step.
-  const int frag0 = col * kKP + hf;
-  // One 32-key column tile: eight fragment reads, 8 x RT MFMAs.
-  auto mfma_tile = [&](f32x16 (&acc)[RT], int tile) {  // tile: (buffer * 64 + column tile * 32) * kKP
-    Frag b[8];
+  // (fp8 rows: 9 slots apart, chunks 4 ks + 2 hf and the next one)
+  const int frag0 = Q8 ? col * KP + 2 * hf : col * KP + hf;
+  // The key fragments of one 32-key column tile (tile: (buffer * 64 + column tile * 32) * KP)
+  // and one matrix instruction of it: row tile rt, k-step ks, onto acc (first: onto zero).
+  struct KeyFrags {
+    Frag b[Q8 ? 1 : 8];
+    Frag8 b8[Q8 ? 2 : 1];
+  };
+  auto load_frags = [&](KeyFrags& f, int tile) {
+    if (Q8) {
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) b[ks].u = (&ktile[0][0])[frag0 + tile + 2 * ks];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        if (ks == 0) {
-          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-          acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b[ks].v, zero, 0, 0, 0);
-        } else {
-          acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b[ks].v, acc[rt], 0, 0, 0);
-        }
+      for (int ks = 0; ks < (Q8 ? 2 : 0); ++ks) {
+        f.b8[ks].u[0] = (&ktile[0][0])[frag0 + tile + 4 * ks];
+        f.b8[ks].u[1] = (&ktile[0][0])[frag0 + tile + 4 * ks + 1];
       }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < (Q8 ? 0 : 8); ++ks) f.b[ks].u = (&ktile[0][0])[frag0 + tile + 2 * ks];
+    }
+  };
+  auto mma = [&](const KeyFrags& f, int rt, int ks, const f32x16& acc, bool first) -> f32x16 {
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if constexpr (Q8)
+      return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8[rt][ks].v, f.b8[ks].v, first ? zero : acc, 0, 0, 0, 0, 0, 0);
+    else
+      return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, f.b[ks].v, first ? zero : acc, 0, 0, 0);
+  };
+  // One 32-key column tile: KS x RT matrix instructions.
+  auto mfma_tile = [&](f32x16 (&acc)[RT], int tile) {
+    KeyFrags f;
+    load_frags(f, tile);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) acc[rt] = mma(f, rt, ks, acc[rt], ks == 0);
   };
   // ReLU, gate, head sum and store of one finished column tile.  PLAIN: every
   // query of the workgroup exists and sees the whole tile, so nothing is masked.
@@ -619,31 +661,27 @@ __device__ __forceinline__ void score_tile_body(
       for (int r = 0; r < 16; ++r) head_term(out, acc, rt, r);
     finish(plain_tag, out, key, scale);
   };
+  constexpr int TPM = 16 / KS;   // head-sum terms that follow each matrix instruction
+  static_assert(KS * RT >= NQL, "one list append per matrix instruction must cover all lists");
   // The matrix instructions of column tile ct into acc_new, each followed by its share
-  // (two accumulator registers) of the head sums of the previous column tile acc_old;
+  // (TPM accumulator registers) of the head sums of the previous column tile acc_old;
   // scheduling barriers pin that order, so a wavefront feeds both pipes at once.
   auto tile_step = [&](auto plain_tag, f32x16 (&acc_new)[RT], int tile,
                        const f32x16 (&acc_old)[RT], int key, float scale) {
-    Frag b[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) b[ks].u = (&ktile[0][0])[frag0 + tile + 2 * ks];
+    KeyFrags f;
+    load_frags(f, tile);
     float out[NQL];
 #pragma unroll
     for (int j = 0; j < NQL; ++j) out[j] = 0.f;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
+    for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        if (ks == 0) {
-          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-          acc_new[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b[ks].v, zero, 0, 0, 0);
-        } else {
-          acc_new[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b[ks].v, acc_new[rt], 0, 0, 0);
-        }
-        const int e = (ks * RT + rt) * 2;   // 8 RT steps x 2 = the 16 RT accumulator registers
-        head_term(out, acc_old, e / 16, e % 16);
-        head_term(out, acc_old, (e + 1) / 16, (e + 1) % 16);
+        acc_new[rt] = mma(f, rt, ks, acc_new[rt], ks == 0);
+        const int e = (ks * RT + rt) * TPM;   // KS RT steps x TPM = the 16 RT accumulator registers
+#pragma unroll
+        for (int u = 0; u < TPM; ++u) head_term(out, acc_old, (e + u) / 16, (e + u) % 16);
         // an empty volatile statement on the running sum keeps these operations between
         // the two scheduling barriers (plain arithmetic would be free to move past them)
         asm volatile("" : "+v"(out[HS == 8 ? (e / 16) * 2 + ((e % 16) >> 3) : (HS == 16 ? e / 16 : 0)]));
@@ -682,26 +720,20 @@ __device__ __forceinline__ void score_tile_body(
   auto filter_step = [&](auto plain_tag, f32x16 (&acc_new)[RT], int tile, const f32x16 (&acc_old)[RT],
                          int key, float scale) {
     constexpr bool PLAIN = decltype(plain_tag)::value;
-    Frag b[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) b[ks].u = (&ktile[0][0])[frag0 + tile + 2 * ks];
+    KeyFrags f;
+    load_frags(f, tile);
     float out[NQL];
 #pragma unroll
     for (int j = 0; j < NQL; ++j) out[j] = 0.f;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
+    for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        if (ks == 0) {
-          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-          acc_new[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b[ks].v, zero, 0, 0, 0);
-        } else {
-          acc_new[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b[ks].v, acc_new[rt], 0, 0, 0);
-        }
-        const int e = (ks * RT + rt) * 2;
-        head_term(out, acc_old, e / 16, e % 16);
-        head_term(out, acc_old, (e + 1) / 16, (e + 1) % 16);
+        acc_new[rt] = mma(f, rt, ks, acc_new[rt], ks == 0);
+        const int e = (ks * RT + rt) * TPM;
+#pragma unroll
+        for (int u = 0; u < TPM; ++u) head_term(out, acc_old, (e + u) / 16, (e + u) % 16);
         if (ks * RT + rt < NQL) append_pending(ks * RT + rt);
         asm volatile("" : "+v"(out[HS == 8 ? (e / 16) * 2 + ((e % 16) >> 3) : (HS == 16 ? e / 16 : 0)]));
         __builtin_amdgcn_sched_barrier(0);
@@ -756,8 +788,8 @@ __device__ __forceinline__ void score_tile_body(
     // leading tiles that need no masks, then the rest
     const int n_plain = min(n_tiles, max(0, (plain_end - k_begin) / kKT));
     auto half = [&](auto tag) {   // tile 0, columns 32..63 | epilogue of its columns 0..31
-      if (FILTER) filter_step(tag, accB, 32 * kKP, accA, k_begin + col, scaleA);
-      else tile_step(tag, accB, 32 * kKP, accA, k_begin + col, scaleA);
+      if (FILTER) filter_step(tag, accB, 32 * KP, accA, k_begin + col, scaleA);
+      else tile_step(tag, accB, 32 * KP, accA, k_begin + col, scaleA);
       if (KDT == MISA_FP8_E4M3) scaleB = kscl[0][32 + col];
     };
     if (n_plain > 0) half(Yes{});
@@ -765,11 +797,11 @@ __device__ __forceinline__ void score_tile_body(
     auto body = [&](auto tag, int j) {
       const int nb = (j + 1) & 1, k0 = k_begin + j * kKT;
       MISA_TILE_LOAD(k0 + 2 * kKT);
-      if (FILTER) filter_step(tag, accA, nb * 64 * kKP, accB, k0 + 32 + col, scaleB);
-      else tile_step(tag, accA, nb * 64 * kKP, accB, k0 + 32 + col, scaleB);
+      if (FILTER) filter_step(tag, accA, nb * 64 * KP, accB, k0 + 32 + col, scaleB);
+      else tile_step(tag, accA, nb * 64 * KP, accB, k0 + 32 + col, scaleB);
       if (KDT == MISA_FP8_E4M3) scaleA = kscl[nb][col];
-      if (FILTER) filter_step(tag, accB, (nb * 64 + 32) * kKP, accA, k0 + kKT + col, scaleA);
-      else tile_step(tag, accB, (nb * 64 + 32) * kKP, accA, k0 + kKT + col, scaleA);
+      if (FILTER) filter_step(tag, accB, (nb * 64 + 32) * KP, accA, k0 + kKT + col, scaleA);
+      else tile_step(tag, accB, (nb * 64 + 32) * KP, accA, k0 + kKT + col, scaleA);
       if (KDT == MISA_FP8_E4M3) scaleB = kscl[nb][32 + col];
       if (FILTER) {
 #pragma unroll
@@ -813,25 +845,25 @@ __device__ __forceinline__ void score_tile_body(
 
 // Two wavefronts per SIMD (at most 256 vector registers) except for 64 head slots, whose
 // four row tiles need the whole register file.
-template <int KDT, int HS, int MODE, bool PAGED>
+template <int KDT, int HS, int MODE, bool PAGED, bool Q8>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HS == 64 ? 1 : 2, HS == 64 ? 1 : 2)))
 void score_tile_kernel(
     Prob p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
     float* __restrict__ S, TileAux aux) {
-  score_tile_body<KDT, HS, MODE, PAGED>(p, keys_per_wg, Q, W, heads, K, kscale, S, aux, blockIdx.y);
+  score_tile_body<KDT, HS, MODE, PAGED, Q8>(p, keys_per_wg, Q, W, heads, K, kscale, S, aux, blockIdx.y);
 }
 
 // Store mode for the flagged query tiles only (aux.run).  Normally none is
 // flagged, so the grid is kept small: blockIdx.y strides over the query tiles.
-template <int KDT, int HS, bool PAGED>
+template <int KDT, int HS, bool PAGED, bool Q8>
 __global__ __launch_bounds__(256) void score_tile_repair_kernel(
     Prob p, int keys_per_wg, int q_tiles, const uint16_t* __restrict__ Q,
     const float* __restrict__ W, const int* __restrict__ heads, const void* __restrict__ K,
     const float* __restrict__ kscale, float* __restrict__ S, TileAux aux) {
   for (int qt = blockIdx.y; qt < q_tiles; qt += gridDim.y) {
     if (!aux.run[blockIdx.z * q_tiles + qt]) continue;
-    score_tile_body<KDT, HS, kTileStore, PAGED>(p, keys_per_wg, Q, W, heads, K, kscale, S, aux, qt);
+    score_tile_body<KDT, HS, kTileStore, PAGED, Q8>(p, keys_per_wg, Q, W, heads, K, kscale, S, aux, qt);
     __syncthreads();
   }
 }
@@ -1006,7 +1038,7 @@ int tile_queries_per_wg(const Prob& p, bool routed) {
   return hc <= 8 ? 32 : (hc <= 16 ? 16 : 8);
 }
 
-template <int KDT, int MODE>
+template <int KDT, int MODE, bool Q8>
 static hipError_t launch_tile(const Prob& p, const void* Q, const float* W, const int* heads,
                               const void* K, const float* kscale, float* S, const TileAux& aux,
                               hipStream_t st) {
@@ -1027,9 +1059,9 @@ static hipError_t launch_tile(const Prob& p, const void* Q, const float* W, cons
     grid.y = (unsigned)std::max(1, std::min(q_tiles, (int)(512 / ((long long)grid.x * p.n_seq))));
 #define GO(HS)                                                                                                      \
   if (p.page_table)                                                                                                 \
-    score_tile_repair_kernel<KDT, HS, true><<<grid, 256, 0, st>>>(p, keys_per_wg, q_tiles, q, W, heads, K, kscale, S, aux); \
+    score_tile_repair_kernel<KDT, HS, true, Q8><<<grid, 256, 0, st>>>(p, keys_per_wg, q_tiles, q, W, heads, K, kscale, S, aux); \
   else                                                                                                              \
-    score_tile_repair_kernel<KDT, HS, false><<<grid, 256, 0, st>>>(p, keys_per_wg, q_tiles, q, W, heads, K, kscale, S, aux)
+    score_tile_repair_kernel<KDT, HS, false, Q8><<<grid, 256, 0, st>>>(p, keys_per_wg, q_tiles, q, W, heads, K, kscale, S, aux)
     switch (hs) {
       case 8: GO(8); break;
       case 16: GO(16); break;
@@ -1041,9 +1073,9 @@ static hipError_t launch_tile(const Prob& p, const void* Q, const float* W, cons
   }
 #define GO(HS)                                                                                               \
   if (p.page_table)                                                                                          \
-    score_tile_kernel<KDT, HS, MODE, true><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S, aux); \
+    score_tile_kernel<KDT, HS, MODE, true, Q8><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S, aux); \
   else                                                                                                       \
-    score_tile_kernel<KDT, HS, MODE, false><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S, aux)
+    score_tile_kernel<KDT, HS, MODE, false, Q8><<<grid, 256, 0, st>>>(p, keys_per_wg, q, W, heads, K, kscale, S, aux)
   switch (hs) {
     case 8: GO(8); break;
     case 16: GO(16); break;
@@ -1054,21 +1086,26 @@ static hipError_t launch_tile(const Prob& p, const void* Q, const float* W, cons
   return hipGetLastError();
 }
 
+// The matrix-core tile kernel takes bf16 queries with bf16 or fp8 keys, and fp8 query codes with
+// fp8 keys (both operands then stay fp8).
 bool tile_path(const Prob& p, int k_dtype, int q_dtype) {
-  return q_dtype == MISA_BF16 && k_dtype != MISA_F32 && p.n_q >= kTileMinQueries;
+  const bool types = (q_dtype == MISA_BF16 && k_dtype != MISA_F32) ||
+                     (q_dtype == MISA_FP8_E4M3 && k_dtype == MISA_FP8_E4M3);
+  return types && p.n_q >= kTileMinQueries;
 }
 
-hipError_t launch_tile_mode(const Prob& p, int k_dtype, int mode, const TileAux& aux, const void* Q,
-                            const float* W, const int* heads, const void* K, const float* kscale,
-                            float* S, hipStream_t st) {
-#define GO(KD)                                                                                     \
-  switch (mode) {                                                                                  \
-    case kTileSample: return launch_tile<KD, kTileSample>(p, Q, W, heads, K, kscale, S, aux, st);   \
-    case kTileFilter: return launch_tile<KD, kTileFilter>(p, Q, W, heads, K, kscale, S, aux, st);   \
-    default: return launch_tile<KD, kTileStore>(p, Q, W, heads, K, kscale, S, aux, st);            \
+hipError_t launch_tile_mode(const Prob& p, int k_dtype, int q_dtype, int mode, const TileAux& aux,
+                            const void* Q, const float* W, const int* heads, const void* K,
+                            const float* kscale, float* S, hipStream_t st) {
+#define GO(KD, Q8)                                                                                      \
+  switch (mode) {                                                                                       \
+    case kTileSample: return launch_tile<KD, kTileSample, Q8>(p, Q, W, heads, K, kscale, S, aux, st);   \
+    case kTileFilter: return launch_tile<KD, kTileFilter, Q8>(p, Q, W, heads, K, kscale, S, aux, st);   \
+    default: return launch_tile<KD, kTileStore, Q8>(p, Q, W, heads, K, kscale, S, aux, st);             \
   }
-  if (k_dtype == MISA_BF16) GO(MISA_BF16)
-  GO(MISA_FP8_E4M3)
+  if (q_dtype == MISA_FP8_E4M3) GO(MISA_FP8_E4M3, true)
+  if (k_dtype == MISA_BF16) GO(MISA_BF16, false)
+  GO(MISA_FP8_E4M3, false)
 #undef GO
 }
 
@@ -1092,9 +1129,10 @@ hipError_t launch_score(const Prob& p, int k_dtype, int q_dtype, const void* Q, 
     if (k_dtype == MISA_BF16) return launch_gather<MISA_BF16>(p, Q, W, K, kscale, cand, k_cand, out, st);
     return launch_gather<MISA_FP8_E4M3>(p, Q, W, K, kscale, cand, k_cand, out, st);
   }
+  if (!cand && tile_path(p, k_dtype, q_dtype))
+    return launch_tile_mode(p, k_dtype, q_dtype, kTileStore, TileAux{}, Q, W, heads, K, kscale, out, st);
+  if (q_dtype == MISA_FP8_E4M3) return hipErrorInvalidValue;   // fp8 codes reach only the tile kernel
   const bool mfma_ok = !cand && q_dtype == MISA_BF16 && k_dtype != MISA_F32;
-  if (mfma_ok && p.n_q >= kTileMinQueries)
-    return launch_tile_mode(p, k_dtype, kTileStore, TileAux{}, Q, W, heads, K, kscale, out, st);
   if (mfma_ok) {
     if (k_dtype == MISA_BF16) return launch_stream<MISA_BF16>(p, Q, W, heads, K, kscale, out, st);
     return launch_stream<MISA_FP8_E4M3>(p, Q, W, heads, K, kscale, out, st);

@@ -417,7 +417,7 @@ hipError_t launch_select(const Prob& p, int k_dtype, int q_dtype, const void* Q,
   int2* cand = reinterpret_cast<int2*>(base + l.cand);
   const dim3 rows(p.n_q, p.n_seq);
 
-  hipError_t e = launch_tile_mode(p, k_dtype, kTileSample, TileAux{}, Q, W, heads, K, kscale, Ss, st);
+  hipError_t e = launch_tile_mode(p, k_dtype, q_dtype, kTileSample, TileAux{}, Q, W, heads, K, kscale, Ss, st);
   if (e != hipSuccess) return e;
   select_threshold_kernel<<<p.n_seq * p.n_q, kThrThreads, 0, st>>>(
       p, Ss, l.m, sample_rank(k), l.cap, l.qwg, l.q_tiles, tau, upper, count, row_flag, tile_flag);
@@ -428,7 +428,7 @@ hipError_t launch_select(const Prob& p, int k_dtype, int q_dtype, const void* Q,
   filter.cand = cand;
   filter.count = count;
   filter.cap = l.cap;
-  e = launch_tile_mode(p, k_dtype, kTileFilter, filter, Q, W, heads, K, kscale, nullptr, st);
+  e = launch_tile_mode(p, k_dtype, q_dtype, kTileFilter, filter, Q, W, heads, K, kscale, nullptr, st);
   if (e != hipSuccess) return e;
 
   const size_t lds = select_lds_bytes(p);  // at most 128 KB (L <= 524288)
@@ -450,7 +450,7 @@ hipError_t launch_select(const Prob& p, int k_dtype, int q_dtype, const void* Q,
   // repair pass, a no-op unless rows were flagged
   TileAux repair;
   repair.run = tile_flag;
-  e = launch_tile_mode(p, k_dtype, kTileStore, repair, Q, W, heads, K, kscale, S, st);
+  e = launch_tile_mode(p, k_dtype, q_dtype, kTileStore, repair, Q, W, heads, K, kscale, S, st);
   if (e != hipSuccess) return e;
   return launch_topk(p, S, p.L, k, nullptr, idx, val, nullptr, st, row_flag);
 }

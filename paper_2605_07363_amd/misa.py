@@ -21,10 +21,10 @@ if not os.path.exists(LIB_PATH):
         "(there is no fallback path)")
 lib = ctypes.CDLL(LIB_PATH)
 
-F32, BF16, FP8_E4M3 = 0, 1, 2
-# Whether fp8 queries with fp8 keys are scored on the fp8 matrix instruction by the prefill kernels
-# (otherwise they are widened to bf16 first); bench.py labels its lines with it.
-HAS_FP8_MFMA = False
+F32, BF16, FP8_E4M3, FP8_E4M3_MATRIX = 0, 1, 2, 3
+# q_dtype FP8_E4M3_MATRIX: fp8 query codes that the prefill scoring kernels may contract with fp8
+# keys on the fp8 matrix instruction (see "fp8 queries" in misa.h); bench.py labels its lines with it.
+HAS_FP8_MFMA = True
 DTYPE_CODES = {"f32": F32, "bf16": BF16, "e4m3": FP8_E4M3}
 OP_POOL, OP_ROUTE, OP_SCORE, OP_TOPK, OP_RERANK, OP_SELECT, OP_HISA = range(7)
 STATUS_NAMES = {0: "MISA_OK", 1: "MISA_ERR_INVALID_ARG", 2: "MISA_ERR_UNSUPPORTED",
@@ -351,6 +351,7 @@ class Indexer:
                  fused=False):
         """fused: stages 3 and 4 run as one select_tokens call and no score matrix is kept."""
         self.p, self.k, self.k_cand, self.fused = p, k, k_cand, fused
+        self.p_score = None     # problem description of the scoring calls when it differs from p (fp8 codes)
         rows = (p.n_seq, p.n_q)
         self.Kp = torch.empty((p.n_seq, p.M, p.d), dtype=torch.float32, device=device)
         self.heads = torch.empty(rows + (p.h,), dtype=torch.int32, device=device)
@@ -380,14 +381,14 @@ class Indexer:
         route_heads(self.p, Q, W, self.Kp, K, kscale, self.heads, self.E, self.ws[OP_ROUTE])
 
     def score(self, Q, W, K, kscale, dense=False):
-        score_tokens(self.p, Q, W, None if dense else self.heads, K, kscale, self.S, self.ws[OP_SCORE])
+        score_tokens(self.p_score or self.p, Q, W, None if dense else self.heads, K, kscale, self.S, self.ws[OP_SCORE])
 
     def select(self):
         topk(self.p, self.S, self.k_cand if self.k_cand else self.k, self.idx1, self.val1,
              self.ws[OP_TOPK])
 
     def select_fused(self, Q, W, K, kscale, dense=False):
-        select_tokens(self.p, Q, W, None if dense else self.heads, K, kscale,
+        select_tokens(self.p_score or self.p, Q, W, None if dense else self.heads, K, kscale,
                       self.k_cand if self.k_cand else self.k, self.idx1, self.val1, self.ws[OP_SELECT])
 
     def refine(self, Q, W, K, kscale):
@@ -396,28 +397,31 @@ class Indexer:
 
     def run(self, K, kscale, Q, W, pool=True):
         """One pass of the whole indexer; returns the selected token indices.  fp8 queries are
-        widened to bf16 once here instead of inside each of the stage calls."""
-        if self.p.q_dtype != FP8_E4M3:
-            return self._run(K, kscale, Q, W, pool)
+        widened to bf16 once here instead of inside each of the stage calls; with q_dtype
+        FP8_E4M3_MATRIX the scoring stage still gets the codes (fp8 matrix instruction)."""
+        if self.p.q_dtype not in (FP8_E4M3, FP8_E4M3_MATRIX):
+            return self._run(K, kscale, Q, W, Q, pool)
         if getattr(self, "_q16", None) is None:
             from dataclasses import replace
             self._q16 = torch.empty(Q.shape, dtype=torch.bfloat16, device=Q.device)
             self._p16 = replace(self.p, q_dtype=BF16)
         convert_queries(self.p, Q, self._q16)
         p8, self.p = self.p, self._p16          # the stage methods below read self.p
+        codes = p8.q_dtype == FP8_E4M3_MATRIX
+        self.p_score = p8 if codes else None
         try:
-            return self._run(K, kscale, self._q16, W, pool)
+            return self._run(K, kscale, self._q16, W, Q if codes else self._q16, pool)
         finally:
-            self.p = p8
+            self.p, self.p_score = p8, None
 
-    def _run(self, K, kscale, Q, W, pool):
+    def _run(self, K, kscale, Q, W, Q_score, pool):
         if pool:
             self.pool(K, kscale)
         self.route(Q, W, K, kscale)
         if self.fused:
-            self.select_fused(Q, W, K, kscale)
+            self.select_fused(Q_score, W, K, kscale)
         else:
-            self.score(Q, W, K, kscale)
+            self.score(Q_score, W, K, kscale)
             self.select()
         if self.k_cand:
             self.refine(Q, W, K, kscale)

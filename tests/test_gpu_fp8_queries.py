@@ -7,7 +7,7 @@ import pytest
 
 from oracle import misa_oracle as O
 from paper_2605_07363_amd import workloads as WL
-from helpers import assert_scores_close, check_index_set, oracle_view
+from helpers import ABS_FRAC_FP8_MATRIX, assert_scores_close, check_index_set, oracle_view
 
 pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
@@ -112,3 +112,85 @@ def test_fp8_queries_whole_pipeline_and_fused_call(misa):
         ref = O.misa(q, w, K, wl.B, wl.h, wl.k, n)
         # a legal head flip inside the tolerance would change the set; at these sizes none occurs
         np.testing.assert_array_equal(got[0, t], ref["tokens"])
+
+
+# ---------------------------------------------------------------- fp8 matrix instruction
+MATRIX_CASES = {
+    # head-slot widths 8, 16, 32 and 64 of the tile kernel, ragged tails, several key ranges
+    "h8": WL.scaled(WL.WORKLOADS["c4"], L=9000, n_q=70, B=64, k=128, k_cand=512, needles=16, q_dtype="e4m3"),
+    "h16": WL.scaled(WL.WORKLOADS["c4"], L=2500, n_q=21, h=16, B=64, k=100, k_cand=300, needles=8, q_dtype="e4m3"),
+    "h32_H32": WL.scaled(WL.WORKLOADS["c4"], L=1100, n_q=13, H=32, h=32, B=32, k=64, k_cand=256, needles=8, q_dtype="e4m3"),
+    "h3": WL.scaled(WL.WORKLOADS["c4"], L=900, n_q=33, h=3, B=16, k=50, k_cand=200, needles=4, q_dtype="e4m3"),
+}
+
+
+@pytest.mark.parametrize("name", list(MATRIX_CASES))
+@pytest.mark.parametrize("paged", [0, 64])
+def test_fp8_matrix_instruction_scores_against_oracle(misa, name, paged):
+    # q_dtype FP8_E4M3_MATRIX with fp8 keys: routed and dense (all heads) scores of the tile kernel
+    # against the oracle on the decoded codes, element by element, under the tolerance of that path
+    wl = MATRIX_CASES[name]
+    inp = WL.make_inputs(wl, seed=77 + sum(map(ord, name)))
+    dv = misa.to_device(inp)
+    if paged:
+        dv = misa.paginate(dv, paged, seed=2)
+    p = replace(dv["problem"], q_dtype=misa.FP8_E4M3_MATRIX)
+    ref_heads = np.zeros((wl.n_seq, wl.n_q, wl.h), dtype=np.int32)
+    views = {}
+    for t in range(wl.n_q):
+        K, q, w, n = views[t] = oracle_view(inp, 0, t)
+        ref_heads[0, t] = O.route_heads(q, w, K, wl.B, wl.h, n)[0]
+    S = torch.full((1, wl.n_q, wl.L), 3.0, dtype=torch.float32, device="cuda")
+    ws = misa.alloc_workspace(p, misa.OP_SCORE)
+    misa.score_tokens(p, dv["Q"], dv["W"], torch.from_numpy(ref_heads).cuda(), dv["K"], dv["kscale"], S, ws)
+    D = torch.empty_like(S)
+    misa.score_tokens(p, dv["Q"], dv["W"], None, dv["K"], dv["kscale"], D, ws)
+    got, dense = S.cpu().numpy(), D.cpu().numpy()
+    for t in range(wl.n_q):
+        K, q, w, n = views[t]
+        assert_scores_close(got[0, t, :n], O.score_tokens(q, w, ref_heads[0, t], K, n), f"S {name} {t}",
+                            abs_frac=ABS_FRAC_FP8_MATRIX)
+        assert_scores_close(dense[0, t, :n], O.dsa_scores(q, w, K, n), f"dense S {name} {t}",
+                            abs_frac=ABS_FRAC_FP8_MATRIX)
+        assert np.all(np.isneginf(got[0, t, n:])) and np.all(np.isneginf(dense[0, t, n:]))
+
+
+def test_fp8_matrix_instruction_pipeline_and_fused_call(misa):
+    # whole MISA-dagger pass with the scoring stage on the codes: fused call = two calls bit for bit,
+    # candidates valid under the margin rule of that path, re-rank against the dense oracle scores
+    wl = WL.scaled(WL.WORKLOADS["c4"], L=16384, n_q=128, B=64, k=256, k_cand=1024, needles=16, q_dtype="e4m3")
+    inp = WL.make_inputs(wl, seed=12)
+    dv = misa.to_device(inp)
+    p = replace(dv["problem"], q_dtype=misa.FP8_E4M3_MATRIX)
+    two = misa.Indexer(p, wl.k, wl.k_cand, want_val=True)
+    a = two.run(dv["K"], dv["kscale"], dv["Q"], dv["W"]).clone()
+    one = misa.Indexer(p, wl.k, wl.k_cand, fused=True, want_val=True)
+    b = one.run(dv["K"], dv["kscale"], dv["Q"], dv["W"]).clone()
+    assert torch.equal(two.idx1, one.idx1) and torch.equal(a, b)
+    assert torch.equal(two.heads, one.heads)
+    heads, cand, fin = two.heads.cpu().numpy(), two.idx1.cpu().numpy(), a.cpu().numpy()
+    S = two.S.cpu().numpy()
+    for t in (0, 1, 63, 64, 127):
+        K, q, w, n = oracle_view(inp, 0, t)
+        ref_S = O.score_tokens(q, w, heads[0, t], K, n)
+        assert_scores_close(S[0, t, :n], ref_S, f"scores {t}", abs_frac=ABS_FRAC_FP8_MATRIX)
+        check_index_set(cand[0, t], ref_S, wl.k_cand, f"candidates {t}", abs_frac=ABS_FRAC_FP8_MATRIX)
+        dense = O.dsa_scores(q, w, K, n)
+        c = cand[0, t][cand[0, t] >= 0]
+        f = fin[0, t][fin[0, t] >= 0]
+        pos = np.searchsorted(c, f)
+        check_index_set(np.concatenate([pos, np.full(wl.k - pos.shape[0], -1, dtype=pos.dtype)]), dense[c], wl.k,
+                        f"re-rank {t}")          # the re-rank runs on the widened queries: default tolerance
+
+
+def test_fp8_matrix_dtype_elsewhere_is_plain_fp8(misa):
+    # decode-shaped problems and bf16 keys do not take the fp8 instruction: results equal those of
+    # q_dtype FP8_E4M3 bit for bit
+    for name in ("decode_fp8_keys", "prefill_bf16_keys"):
+        wl = CASES[name]
+        dv = misa.to_device(WL.make_inputs(wl, seed=5))
+        p = dv["problem"]
+        a = stages(misa, wl, p, dv["K"], dv["kscale"], dv["Q"], dv["W"])
+        b = stages(misa, wl, replace(p, q_dtype=misa.FP8_E4M3_MATRIX), dv["K"], dv["kscale"], dv["Q"], dv["W"])
+        for key in a:
+            assert torch.equal(a[key], b[key]), (name, key)

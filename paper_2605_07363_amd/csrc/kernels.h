@@ -41,7 +41,7 @@ struct TileAux {
   int cap = 0;
 };
 bool tile_path(const Prob& p, int k_dtype, int q_dtype);  // launch_score uses the tile kernel
-int tile_queries_per_wg(const Prob& p, bool routed);
+int tile_queries_per_wg(const Prob& p, bool routed, bool q8);  // q8: fp8 query codes (fp8 matrix instruction)
 // q_dtype: MISA_BF16, or MISA_FP8_E4M3 (codes, with fp8 keys only: contracted on the fp8 matrix instruction)
 hipError_t launch_tile_mode(const Prob& p, int k_dtype, int q_dtype, int mode, const TileAux& aux,
                             const void* Q, const float* W, const int* heads, const void* K,

@@ -321,9 +321,14 @@ __global__ __launch_bounds__(256) void score_stream_kernel(
 //   workgroups that share a key range run on the same XCD and its L2.
 //
 // HS = head slots per query (h rounded up to 8, 16, 32 or 64).
-template <int HS>
+// WIDE (fp8 operands, 8 head slots, scores stored): four row tiles as well - the operands are half
+// as wide, and that kernel is bound by the vector work per key tile, which a wavefront with 16
+// queries shares over twice as many products (0.40 ms against 0.46 ms on the 131072-key prefill
+// workload).  The filter mode stays with two (its list work needs the second wavefront per SIMD
+// to hide behind: 0.99 ms against 0.67 ms for the fused call with four).
+template <int HS, bool WIDE>
 struct TileGeom {
-  static constexpr int RT = HS <= 32 ? 2 : 4;   // 32-row tiles per wavefront
+  static constexpr int RT = (HS > 32 || (WIDE && HS == 8)) ? 4 : 2;   // 32-row tiles per wavefront
   static constexpr int QW = RT * 32 / HS;       // queries per wavefront
   static constexpr int QWG = 4 * QW;            // queries per workgroup
   // query (within the wavefront) and head slot of accumulator register r of
@@ -365,7 +370,7 @@ __device__ __forceinline__ void score_tile_body(
     const Prob& p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
     float* __restrict__ S, const TileAux& aux, int q_tile) {
-  using G = TileGeom<HS>;
+  using G = TileGeom<HS, Q8 && MODE == kTileStore>;
   constexpr int RT = G::RT, QW = G::QW, QWG = G::QWG;
   constexpr bool FILTER = MODE == kTileFilter, SAMPLE = MODE == kTileSample;
   constexpr int NQL_ = HS == 8 ? RT * 2 : (HS == 16 ? RT : 1);  // queries per lane
@@ -843,10 +848,10 @@ __device__ __forceinline__ void score_tile_body(
   }
 }
 
-// Two wavefronts per SIMD (at most 256 vector registers) except for 64 head slots, whose
-// four row tiles need the whole register file.
+// Two wavefronts per SIMD (at most 256 vector registers) except with four row tiles, which
+// need the whole register file.
 template <int KDT, int HS, int MODE, bool PAGED, bool Q8>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HS == 64 ? 1 : 2, HS == 64 ? 1 : 2)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TileGeom<HS, Q8 && MODE == kTileStore>::RT == 4 ? 1 : 2, TileGeom<HS, Q8 && MODE == kTileStore>::RT == 4 ? 1 : 2)))
 void score_tile_kernel(
     Prob p, int keys_per_wg, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const int* __restrict__ heads, const void* __restrict__ K, const float* __restrict__ kscale,
@@ -1033,9 +1038,10 @@ static hipError_t launch_stream(const Prob& p, const void* Q, const float* W, co
   return hipGetLastError();
 }
 
-int tile_queries_per_wg(const Prob& p, bool routed) {
+// q8: the store-mode geometry of fp8 query codes (the wider query tile)
+int tile_queries_per_wg(const Prob& p, bool routed, bool q8) {
   const int hc = routed ? p.h : p.H;
-  return hc <= 8 ? 32 : (hc <= 16 ? 16 : 8);
+  return hc <= 8 ? (q8 ? 64 : 32) : (hc <= 16 ? 16 : 8);
 }
 
 template <int KDT, int MODE, bool Q8>
@@ -1044,7 +1050,7 @@ static hipError_t launch_tile(const Prob& p, const void* Q, const float* W, cons
                               hipStream_t st) {
   const int hc = heads ? p.h : p.H;
   const int hs = hc <= 8 ? 8 : (hc <= 16 ? 16 : (hc <= 32 ? 32 : 64));
-  const int qwg = tile_queries_per_wg(p, heads != nullptr);
+  const int qwg = tile_queries_per_wg(p, heads != nullptr, Q8 && MODE == kTileStore);
   const int q_tiles = (p.n_q + qwg - 1) / qwg;
   const int lt = MODE == kTileSample ? p.L / kSampleStride : p.L;  // keys in tile space
   // Key ranges: a multiple of 8 (one set per XCD), enough workgroups to fill

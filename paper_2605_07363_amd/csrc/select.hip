@@ -360,12 +360,12 @@ struct Layout {
 
 size_t up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-Layout layout(const Prob& p, bool routed, int k) {
+Layout layout(const Prob& p, bool routed, int k, bool q8 = false) {
   Layout l;
   const size_t rows = (size_t)p.n_seq * p.n_q;
   l.m = p.L / kSampleStride;
   l.cap = list_capacity(k);
-  l.qwg = tile_queries_per_wg(p, routed);
+  l.qwg = tile_queries_per_wg(p, routed, q8);
   l.q_tiles = (p.n_q + l.qwg - 1) / l.qwg;
   size_t o = 0;
   l.S = o;         o += up(rows * p.L * sizeof(float));
@@ -406,7 +406,7 @@ hipError_t launch_select(const Prob& p, int k_dtype, int q_dtype, const void* Q,
     if (e != hipSuccess) return e;
     return launch_topk(p, S, p.L, k, nullptr, idx, val, base + dense, st);
   }
-  const Layout l = layout(p, heads != nullptr, k);
+  const Layout l = layout(p, heads != nullptr, k, q_dtype == MISA_FP8_E4M3);
   float* S = reinterpret_cast<float*>(base + l.S);
   float* Ss = reinterpret_cast<float*>(base + l.sample);
   float* tau = reinterpret_cast<float*>(base + l.tau);

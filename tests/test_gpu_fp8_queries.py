@@ -194,3 +194,40 @@ def test_fp8_matrix_dtype_elsewhere_is_plain_fp8(misa):
         b = stages(misa, wl, replace(p, q_dtype=misa.FP8_E4M3_MATRIX), dv["K"], dv["kscale"], dv["Q"], dv["W"])
         for key in a:
             assert torch.equal(a[key], b[key]), (name, key)
+
+
+@pytest.mark.parametrize("sampled_are", ["high", "low"])
+def test_fp8_matrix_fused_call_repairs_rows_with_misleading_samples(misa, sampled_are):
+    # As for bf16 queries: the keys at the sampled positions are made 64x larger (or smaller) than the
+    # others through their per-token scale and all gates positive, so the sampled threshold is far too
+    # high or far too low; the fused call must repair every row (its store-mode pass runs on query
+    # tiles of 64 here, the filter pass on tiles of 32) and equal the two calls bit for bit.
+    wl = WL.scaled(WL.WORKLOADS["c4"], L=40000, n_q=70, k=1024, k_cand=0, needles=0, q_dtype="e4m3")
+    inp = WL.make_inputs(wl, seed=9)
+    pos = np.array([16 * j + (((j * 2654435761) & 0xFFFFFFFF) >> 28) for j in range(wl.L // 16)])
+    factor = np.full(wl.L, 1.0 if sampled_are == "high" else 64.0, dtype=np.float32)
+    factor[pos] = 64.0 if sampled_are == "high" else 1.0
+    inp["kscale"] = (inp["kscale"] * factor[None, :]).astype(np.float32)
+    inp["W"] = np.abs(inp["W"]) + 0.01
+    dv = misa.to_device(inp)
+    p = replace(dv["problem"], q_dtype=misa.FP8_E4M3_MATRIX)
+    rng = np.random.default_rng(3)
+    heads = torch.from_numpy(np.stack([np.sort(rng.choice(wl.H, wl.h, replace=False)) for _ in range(wl.n_q)])
+                             .reshape(1, wl.n_q, wl.h).astype(np.int32)).cuda()
+    rows = (1, wl.n_q)
+    S = torch.empty(rows + (wl.L,), dtype=torch.float32, device="cuda")
+    ref_idx = torch.full(rows + (wl.k,), -9, dtype=torch.int32, device="cuda")
+    ref_val = torch.full(rows + (wl.k,), 9.0, dtype=torch.float32, device="cuda")
+    misa.score_tokens(p, dv["Q"], dv["W"], heads, dv["K"], dv["kscale"], S, misa.alloc_workspace(p, misa.OP_SCORE))
+    misa.topk(p, S, wl.k, ref_idx, ref_val, misa.alloc_workspace(p, misa.OP_TOPK, wl.k))
+    idx, val = torch.full_like(ref_idx, -9), torch.full_like(ref_val, 9.0)
+    ws = misa.alloc_workspace(p, misa.OP_SELECT, wl.k)
+    ws.fill_(0xA5)
+    misa.select_tokens(p, dv["Q"], dv["W"], heads, dv["K"], dv["kscale"], wl.k, idx, val, ws)
+    assert torch.equal(idx, ref_idx) and torch.equal(val, ref_val)
+    assert int(misa.select_repaired_rows(p, True, wl.k, ws).sum()) == wl.n_q
+    got, hs = idx.cpu().numpy(), heads.cpu().numpy()
+    for t in (0, 63, 64, 69):
+        K, q, w, n = oracle_view(inp, 0, t)
+        check_index_set(got[0, t], O.score_tokens(q, w, hs[0, t], K, n), wl.k, f"repaired row {t}",
+                        abs_frac=ABS_FRAC_FP8_MATRIX)

@@ -115,8 +115,8 @@ def measure(args, name: str, fused: bool, main_line: bool) -> dict:
         dv = misa.paginate(dv, args.paged, seed=1)
     p = dv["problem"]
     Q, W = dv["Q"], dv["W"]
-    # fp8 queries: a step widens them to bf16 once; prefill workloads with fp8 keys score on the
-    # codes themselves (fp8 matrix instruction), routing and re-ranking use the widened copy
+    # fp8 queries: a step widens them to bf16 once; prefill workloads with fp8 keys score and re-rank
+    # on the codes themselves (fp8 matrix instruction), routing uses the widened copy
     native_fp8 = bool(args.fp8_queries) and wl.k_dtype == "e4m3" and not wl.decode and misa.HAS_FP8_MFMA
     Q8, p8 = None, None
     widen = bool(args.fp8_queries)
@@ -149,7 +149,7 @@ def measure(args, name: str, fused: bool, main_line: bool) -> dict:
         pool = (lambda: ix.pool_update(K, ks, newest, 1)) if incremental else (lambda: ix.pool(K, ks))
         calls = ([lambda: misa.convert_queries(p8, Q8, Q)] if widen else []) + \
             [pool, lambda: ix.route(Q, W, K, ks)] + mid + \
-            ([lambda: ix.refine(Q, W, K, ks)] if wl.k_cand else [])
+            ([lambda: ix.refine(Qs, W, K, ks)] if wl.k_cand else [])
         for j, c in enumerate(calls):
             if ev is not None:
                 ev[j][0].record()

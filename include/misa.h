@@ -344,7 +344,8 @@ misa_status misa_block_sparse_select(const misa_problem* p, const void* Q, const
  *
  * q_dtype = MISA_FP8_E4M3_MATRIX is the same input format, with one permission: when the keys
  * are MISA_FP8_E4M3 too and the problem has at least 8 queries per sequence (the prefill tile
- * kernel), misa_score_tokens and misa_select_tokens leave queries and keys as codes and
+ * kernel), misa_score_tokens and misa_select_tokens - and misa_rerank for any number of
+ * queries - leave queries and keys as codes and
  * contract them with the fp8 matrix instruction (v_mfma_f32_32x32x64_f8f6f4): half the matrix
  * time, no widening, half the staged bytes.  The products are still exact, but that
  * instruction sums its 64 products in a narrower format than fp32: measured on MI355X, a dot
@@ -352,7 +353,8 @@ misa_status misa_block_sparse_select(const misa_problem* p, const void* Q, const
  * accumulation of the widened values: 2^-22).  Scores therefore carry an absolute error of up
  * to about 4e-5 of the largest score magnitudes of their row instead of 1e-5, and selections
  * may differ from the exact ones among scores that close.  All other calls (routing,
- * re-ranking, decode-shaped problems, other key types) treat it exactly as MISA_FP8_E4M3.
+ * decode-shaped scoring, other key types, the comparison indexers) treat it exactly as
+ * MISA_FP8_E4M3.
  *   Q       in   [n_seq, n_q, H, d] uint8, 16-byte aligned (p->q_dtype must be an fp8 type)
  *   Q_bf16  out  [n_seq, n_q, H, d] bf16, 16-byte aligned
  */

@@ -379,7 +379,9 @@ misa_status misa_rerank(const misa_problem* p, const void* Q, const float* W, co
   if (k_cand > misa::kMaxTopK)
     return fail(MISA_ERR_UNSUPPORTED, "k_cand must be <= 16384 (got %d)", k_cand);
   QView qv;
-  if ((st = stage_queries(p, Q, ws_bytes_for(pr, MISA_OP_RERANK, k_cand), ws, ws_bytes, stream, &qv)) != MISA_OK) return st;
+  // the candidate gather takes fp8 codes with fp8 keys for any number of queries
+  const bool native = p->q_dtype == MISA_FP8_E4M3_MATRIX && p->k_dtype == MISA_FP8_E4M3;
+  if ((st = stage_queries(p, Q, ws_bytes_for(pr, MISA_OP_RERANK, k_cand), ws, ws_bytes, stream, &qv, native)) != MISA_OK) return st;
   float* dense = static_cast<float*>(qv.ws);
   hipError_t e = misa::launch_score(pr, p->k_dtype, qv.q_dtype, qv.Q, W, nullptr, K, kscale, cand, k_cand,
                                     dense, (hipStream_t)stream);

@@ -883,7 +883,7 @@ __global__ __launch_bounds__(256) void score_tile_repair_kernel(
 // in-lane over its accumulator registers plus one exchange between half-waves.
 constexpr int kGatherChunk = 2048;  // candidates per workgroup
 
-template <int KDT, int RT>
+template <int KDT, int RT, bool Q8>
 __global__ __launch_bounds__(256) void score_gather_kernel(
     Prob p, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const void* __restrict__ K, const float* __restrict__ kscale, const int* __restrict__ cand,
@@ -907,16 +907,31 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
 
   // Row m of tile rt is head rt*32 + m; half-wave hf holds components 64 hf .. 64 hf + 63,
   // k-step ks the eight from 64 hf + 8 ks (the key fragments use the same mapping).
-  Frag a[RT][8];
+  // Q8 (fp8 query codes and fp8 keys, fp8 matrix instruction): k-step ks of 64 components,
+  // half-wave hf the 32 from 64 ks + 32 hf.
+  static_assert(!Q8 || KDT == MISA_FP8_E4M3, "fp8 queries contract with fp8 keys only");
+  Frag a[RT][Q8 ? 1 : 8];
+  Frag8 a8[RT][Q8 ? 2 : 1];
   __shared__ float s_gate[2][RT * 16];   // [half-wave][accumulator register]: gates of the rows a lane holds
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
     const int head = rt * 32 + col;
-    const uint16_t* src = Q + (qrow * p.H + min(head, p.H - 1)) * kD + 64 * hf;
+    if (Q8) {
+      const uint8_t* src = reinterpret_cast<const uint8_t*>(Q) + (qrow * p.H + min(head, p.H - 1)) * kD + 32 * hf;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const uint4 v = *reinterpret_cast<const uint4*>(src + 8 * ks);
-      a[rt][ks].u = head < p.H ? v : make_uint4(0, 0, 0, 0);
+      for (int ks = 0; ks < (Q8 ? 2 : 0); ++ks)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const uint4 v = *reinterpret_cast<const uint4*>(src + 64 * ks + 16 * u);
+          a8[rt][ks].u[u] = head < p.H ? v : make_uint4(0, 0, 0, 0);
+        }
+    } else {
+      const uint16_t* src = Q + (qrow * p.H + min(head, p.H - 1)) * kD + 64 * hf;
+#pragma unroll
+      for (int ks = 0; ks < (Q8 ? 0 : 8); ++ks) {
+        const uint4 v = *reinterpret_cast<const uint4*>(src + 8 * ks);
+        a[rt][ks].u = head < p.H ? v : make_uint4(0, 0, 0, 0);
+      }
     }
   }
   if (threadIdx.x < 2 * RT * 16) {
@@ -935,9 +950,9 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
     r.s = s;
     const int row = max(s, 0);
     const size_t kslot = key_slot(p, seq, row);
-    const uint4* src = reinterpret_cast<const uint4*>(static_cast<const char*>(K) + kslot * ROW_BYTES + hf * (ROW_BYTES / 2));
+    const uint4* src = reinterpret_cast<const uint4*>(static_cast<const char*>(K) + kslot * ROW_BYTES + hf * (Q8 ? 32 : ROW_BYTES / 2));
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) r.v[i] = src[i];
+    for (int i = 0; i < NLD; ++i) r.v[i] = src[Q8 ? 4 * (i >> 1) + (i & 1) : i];   // Q8: chunks 0, 1 and 4, 5 from 32 hf
     r.scale = 1.f;
     if (KDT == MISA_FP8_E4M3) r.scale = kscale[kslot];
   };
@@ -948,19 +963,31 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[rt][q] = 0.f;
+    if constexpr (Q8) {
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      Frag b;
-      if (KDT == MISA_BF16) {
-        b.u = r.v[ks % NLD];
-      } else {
-        const uint4 w = r.v[(ks >> 1) % NLD];
-        fp8x4_to_bf16x4((ks & 1) ? w.z : w.x, b.w[0], b.w[1]);
-        fp8x4_to_bf16x4((ks & 1) ? w.w : w.y, b.w[2], b.w[3]);
+      for (int ks = 0; ks < 2; ++ks) {
+        Frag8 b;
+        b.u[0] = r.v[(2 * ks) % NLD];
+        b.u[1] = r.v[(2 * ks + 1) % NLD];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+          acc[rt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8[rt][ks].v, b.v, acc[rt], 0, 0, 0, 0, 0, 0);
       }
+    } else {
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt)
-        acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b.v, acc[rt], 0, 0, 0);
+      for (int ks = 0; ks < 8; ++ks) {
+        Frag b;
+        if (KDT == MISA_BF16) {
+          b.u = r.v[ks % NLD];
+        } else {
+          const uint4 w = r.v[(ks >> 1) % NLD];
+          fp8x4_to_bf16x4((ks & 1) ? w.z : w.x, b.w[0], b.w[1]);
+          fp8x4_to_bf16x4((ks & 1) ? w.w : w.y, b.w[2], b.w[3]);
+        }
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+          acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rt][ks].v, b.v, acc[rt], 0, 0, 0);
+      }
     }
     float sum = 0.f;
 #pragma unroll
@@ -1115,25 +1142,27 @@ hipError_t launch_tile_mode(const Prob& p, int k_dtype, int q_dtype, int mode, c
 #undef GO
 }
 
-template <int KDT>
+template <int KDT, bool Q8>
 static hipError_t launch_gather(const Prob& p, const void* Q, const float* W, const void* K,
                                 const float* kscale, const int* cand, int k_cand, float* out,
                                 hipStream_t st) {
   const dim3 grid((k_cand + kGatherChunk - 1) / kGatherChunk, p.n_q, p.n_seq);
   const uint16_t* q = static_cast<const uint16_t*>(Q);
   if (p.H <= 32)
-    score_gather_kernel<KDT, 1><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, out);
+    score_gather_kernel<KDT, 1, Q8><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, out);
   else
-    score_gather_kernel<KDT, 2><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, out);
+    score_gather_kernel<KDT, 2, Q8><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, out);
   return hipGetLastError();
 }
 
 hipError_t launch_score(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,
                         const int* heads, const void* K, const float* kscale, const int* cand,
                         int k_cand, float* out, hipStream_t st) {
+  if (cand && !heads && q_dtype == MISA_FP8_E4M3 && k_dtype == MISA_FP8_E4M3)
+    return launch_gather<MISA_FP8_E4M3, true>(p, Q, W, K, kscale, cand, k_cand, out, st);
   if (cand && !heads && q_dtype == MISA_BF16 && k_dtype != MISA_F32) {
-    if (k_dtype == MISA_BF16) return launch_gather<MISA_BF16>(p, Q, W, K, kscale, cand, k_cand, out, st);
-    return launch_gather<MISA_FP8_E4M3>(p, Q, W, K, kscale, cand, k_cand, out, st);
+    if (k_dtype == MISA_BF16) return launch_gather<MISA_BF16, false>(p, Q, W, K, kscale, cand, k_cand, out, st);
+    return launch_gather<MISA_FP8_E4M3, false>(p, Q, W, K, kscale, cand, k_cand, out, st);
   }
   if (!cand && tile_path(p, k_dtype, q_dtype))
     return launch_tile_mode(p, k_dtype, q_dtype, kTileStore, TileAux{}, Q, W, heads, K, kscale, out, st);

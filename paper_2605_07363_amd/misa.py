@@ -392,7 +392,7 @@ class Indexer:
                       self.k_cand if self.k_cand else self.k, self.idx1, self.val1, self.ws[OP_SELECT])
 
     def refine(self, Q, W, K, kscale):
-        rerank(self.p, Q, W, K, kscale, self.idx1, self.k_cand, self.k, self.idx, self.val,
+        rerank(self.p_score or self.p, Q, W, K, kscale, self.idx1, self.k_cand, self.k, self.idx, self.val,
                self.ws[OP_RERANK])
 
     def run(self, K, kscale, Q, W, pool=True):
@@ -424,5 +424,5 @@ class Indexer:
             self.score(Q_score, W, K, kscale)
             self.select()
         if self.k_cand:
-            self.refine(Q, W, K, kscale)
+            self.refine(Q_score, W, K, kscale)
         return self.idx

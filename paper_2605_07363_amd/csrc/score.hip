@@ -881,13 +881,17 @@ __global__ __launch_bounds__(256) void score_tile_repair_kernel(
 // candidate keys per step straight from the (cache-resident) key cache into
 // MFMA fragments - a lane reads one contiguous half row - and the head sum is
 // in-lane over its accumulator registers plus one exchange between half-waves.
-constexpr int kGatherChunk = 2048;  // candidates per workgroup
+// Candidates per workgroup: at most kGatherChunk.  The set-up of a workgroup (head rows, gates,
+// candidate indices) costs about a fifth of the kernel with 2048 candidates each, so many-query
+// problems take 4096 (0.37 ms against 0.39 ms on the 2048 x 8192 re-rank); few-query problems
+// take shorter pieces to put more workgroups on the chip.
+constexpr int kGatherChunk = 4096;
 
 template <int KDT, int RT, bool Q8>
 __global__ __launch_bounds__(256) void score_gather_kernel(
     Prob p, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const void* __restrict__ K, const float* __restrict__ kscale, const int* __restrict__ cand,
-    int k_cand, float* __restrict__ out) {
+    int k_cand, int chunk, float* __restrict__ out) {
   constexpr int ROW_BYTES = KDT == MISA_BF16 ? 256 : 128;
   constexpr int NLD = KDT == MISA_BF16 ? 8 : 4;  // 16-byte loads per lane and key (half a row)
   const int t = blockIdx.y, seq = blockIdx.z;
@@ -895,15 +899,15 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
   const int col = lane & 31, hf = lane >> 5;
   const int n = visible(p, seq, t);
   const size_t qrow = (size_t)seq * p.n_q + t;
-  const int c_begin = blockIdx.x * kGatherChunk;
-  const int c_end = min(c_begin + kGatherChunk, k_cand);
+  const int c_begin = blockIdx.x * chunk;            // chunk: a multiple of 128, at most kGatherChunk
+  const int c_end = min(c_begin + chunk, k_cand);
   const int* crow = cand + qrow * k_cand;
   float* orow = out + qrow * k_cand;
 
   // The candidate indices of this workgroup go through LDS, so that reading them
   // in the loop does not wait on the key loads in flight.
   __shared__ int s_cand[kGatherChunk];
-  for (int i = threadIdx.x; i < kGatherChunk; i += 256) s_cand[i] = c_begin + i < c_end ? crow[c_begin + i] : -1;
+  for (int i = threadIdx.x; i < chunk; i += 256) s_cand[i] = c_begin + i < c_end ? crow[c_begin + i] : -1;
 
   // Row m of tile rt is head rt*32 + m; half-wave hf holds components 64 hf .. 64 hf + 63,
   // k-step ks the eight from 64 hf + 8 ks (the key fragments use the same mapping).
@@ -945,7 +949,7 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
   struct Raw { uint4 v[NLD]; float scale; int s; };
   auto issue = [&](Raw& r, int c0) {
     const int slot = c0 + col;
-    int s = s_cand[min(slot - c_begin, kGatherChunk - 1)];
+    int s = s_cand[min(slot - c_begin, chunk - 1)];
     if (slot >= c_end || s >= n) s = -1;
     r.s = s;
     const int row = max(s, 0);
@@ -1146,12 +1150,17 @@ template <int KDT, bool Q8>
 static hipError_t launch_gather(const Prob& p, const void* Q, const float* W, const void* K,
                                 const float* kscale, const int* cand, int k_cand, float* out,
                                 hipStream_t st) {
-  const dim3 grid((k_cand + kGatherChunk - 1) / kGatherChunk, p.n_q, p.n_seq);
+  // pieces of 512 .. kGatherChunk candidates (a step of the four wavefronts covers 128): halved
+  // while fewer than 1024 workgroups would result
+  int chunk = kGatherChunk;
+  const long long rows = (long long)p.n_q * p.n_seq;
+  while (chunk > 512 && rows * ((k_cand + chunk - 1) / chunk) < 1024) chunk /= 2;
+  const dim3 grid((k_cand + chunk - 1) / chunk, p.n_q, p.n_seq);
   const uint16_t* q = static_cast<const uint16_t*>(Q);
   if (p.H <= 32)
-    score_gather_kernel<KDT, 1, Q8><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, out);
+    score_gather_kernel<KDT, 1, Q8><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, chunk, out);
   else
-    score_gather_kernel<KDT, 2, Q8><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, out);
+    score_gather_kernel<KDT, 2, Q8><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, chunk, out);
   return hipGetLastError();
 }
 

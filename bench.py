@@ -9,8 +9,9 @@ synthetic inputs that are already resident in HBM.  Prints ONE JSON line.
 
 The default run times the long-decode workload c3 (the HBM half of the metric:
 `value`, `roofline`) and then, in the same process, the MISA-dagger prefill
-workload c4 at the same L = 131072 (the matrix-core half: object `prefill`),
-once as five calls and once with scoring and top-k fused.  Every number in the
+workload c4 at the same L = 131072 (the matrix-core half: object `prefill`)
+and the single-stage prefill chunk c2 (object `prefill_single_stage`), each
+once as separate calls and once with scoring and top-k fused.  Every number in the
 line is measured by this run except where a field says otherwise.
 """
 from __future__ import annotations
@@ -368,33 +369,42 @@ def main() -> int:
     }
 
     if default_run and not args.no_prefill:
-        # The matrix-core half of the metric at the same L: the MISA-dagger prefill workload,
-        # as five calls (score_tile_kernel writes the score matrix) and with scoring + top-k fused.
+        # The matrix-core half of the metric: the MISA-dagger prefill workload at the same L (c4) and
+        # the single-stage DeepSeek-V3.2-shaped chunk (c2), each as separate calls
+        # (score_tile_kernel writes the score matrix) and with scoring + top-k fused.
         import copy
         pargs = copy.copy(args)
         pargs.steps, pargs.warmup = min(args.steps, 10), min(args.warmup, 2)
-        two = measure(pargs, "c4", False, False)
-        one = measure(pargs, "c4", True, False)
-        r2, r1 = roofline_of(two, peaks), roofline_of(one, peaks)
-        rerank_flops = 2.0 * two["wl"].n_seq * two["wl"].n_q * two["wl"].k_cand * two["wl"].H * two["wl"].d
-        out["prefill"] = {
-            "workload": two["workload"], "pairs_per_step": two["pairs"], "dtype": two["dtype"],
-            "steps": pargs.steps, "warmup": pargs.warmup,
-            "ms_per_step": two["ms_per_step"], "value_pairs_per_s": two["pairs"] / (two["ms_per_step"] * 1e-3),
-            "stage_ms": two["stage_ms"], "ms_per_step_excl_pool": two["ms_per_step_excl_pool"],
-            "roofline": r2,
-            "score_tile_ms": two["stage_ms"]["score"],
-            "rerank_ms": two["stage_ms"]["rerank"],
-            "rerank_TFLOPs": rerank_flops / (two["stage_ms"]["rerank"] * 1e-3) / 1e12,
-            "rerank_frac_of_bf16_peak": rerank_flops / (two["stage_ms"]["rerank"] * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS["bf16"],
-            "fused": {"ms_per_step": one["ms_per_step"], "stage_ms": one["stage_ms"],
-                      "fused_select_ms": one["stage_ms"]["select"], "roofline": r1,
-                      "value_pairs_per_s": one["pairs"] / (one["ms_per_step"] * 1e-3)},
-            "recall_of_dense_topk": two["recall"], "iou_with_dense_topk": two["iou"],
-            "dense_dsa_ms": two["dense_dsa_ms"],
-            "speedup_vs_dense": two["speedup_vs_dense"],
-            "speedup_vs_dense_fused": one["speedup_vs_dense"],
-        }
+
+        def prefill_object(name):
+            two = measure(pargs, name, False, False)
+            one = measure(pargs, name, True, False)
+            r2, r1 = roofline_of(two, peaks), roofline_of(one, peaks)
+            w = two["wl"]
+            obj = {
+                "workload": two["workload"], "pairs_per_step": two["pairs"], "dtype": two["dtype"],
+                "steps": pargs.steps, "warmup": pargs.warmup,
+                "ms_per_step": two["ms_per_step"], "value_pairs_per_s": two["pairs"] / (two["ms_per_step"] * 1e-3),
+                "stage_ms": two["stage_ms"], "ms_per_step_excl_pool": two["ms_per_step_excl_pool"],
+                "roofline": r2,
+                "score_tile_ms": two["stage_ms"]["score"],
+                "fused": {"ms_per_step": one["ms_per_step"], "stage_ms": one["stage_ms"],
+                          "fused_select_ms": one["stage_ms"]["select"], "roofline": r1,
+                          "value_pairs_per_s": one["pairs"] / (one["ms_per_step"] * 1e-3)},
+                "recall_of_dense_topk": two["recall"], "iou_with_dense_topk": two["iou"],
+                "dense_dsa_ms": two["dense_dsa_ms"],
+                "speedup_vs_dense": two["speedup_vs_dense"],
+                "speedup_vs_dense_fused": one["speedup_vs_dense"],
+            }
+            if w.k_cand:
+                flops = 2.0 * w.n_seq * w.n_q * w.k_cand * w.H * w.d
+                obj["rerank_ms"] = two["stage_ms"]["rerank"]
+                obj["rerank_TFLOPs"] = flops / (obj["rerank_ms"] * 1e-3) / 1e12
+                obj["rerank_frac_of_bf16_peak"] = obj["rerank_TFLOPs"] / MFMA_PEAK_TFLOPS["bf16"]
+            return obj
+
+        out["prefill"] = prefill_object("c4")
+        out["prefill_single_stage"] = prefill_object("c2")
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, m["inp"])

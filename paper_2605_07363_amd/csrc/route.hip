@@ -3,8 +3,8 @@
 // route_tile_kernel (bf16 queries): the [queries x heads, 128] x [128, blocks]
 // product runs on the matrix core.  Query-head rows are the stationary operand
 // (registers); the fp32 pooled keys stream through LDS as two bf16 tiles, the
-// upper 16 bits of each value and the remainder, and both are multiplied, so
-// the products carry ~16 mantissa bits of the pooled key.  ReLU, the causal
+// bf16 nearest to each value and the bf16 nearest to the exact remainder, and
+// both are multiplied, so the products carry the pooled key to 2^-17 relative.  ReLU, the causal
 // block mask and the sum over blocks stay in accumulator lanes until the end
 // of the block range, when one wavefront reduction per row writes the partial
 // sum to the workspace.

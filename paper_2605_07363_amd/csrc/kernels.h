@@ -36,10 +36,14 @@ constexpr int kSampleStride = 16;
 struct TileAux {
   const int* run = nullptr;     // store mode: per query tile, 0 = skip the tile (nullptr: run all)
   const float* tau = nullptr;   // filter mode: per-row score threshold
-  int2* cand = nullptr;         // filter mode: [rows, cap] (key index, score bits)
-  int* count = nullptr;         // filter mode: per-row candidate count (may exceed cap: overflow)
-  int cap = 0;
+  int2* cand = nullptr;         // filter mode: [rows, cap] (key index, score bits), cut into segments
+  const int* seg = nullptr;     // filter mode: [rows, ranges + 1] segment offsets inside a row's list
+  int* seg_count = nullptr;     // filter mode: [rows, ranges] hits of a key range (may exceed its segment: overflow)
+  int cap = 0;                  // filter mode: list entries per row
+  int ranges = 0;               // filter mode: key ranges = workgroups along x of the launch
 };
+// Key ranges (workgroups along x) and keys per range of the tile kernel's launch in a mode.
+int tile_key_ranges(const Prob& p, bool routed, bool q8, int mode, int* keys_per_wg);
 bool tile_path(const Prob& p, int k_dtype, int q_dtype);  // launch_score uses the tile kernel
 int tile_queries_per_wg(const Prob& p, bool routed, bool q8);  // q8: fp8 query codes (fp8 matrix instruction)
 // q_dtype: MISA_BF16, or MISA_FP8_E4M3 (codes, with fp8 keys only: contracted on the fp8 matrix instruction)

@@ -133,6 +133,19 @@ __device__ __forceinline__ uint4 buffer_load16(BufferRsrc r, uint32_t lane_off, 
   const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)wave_off, 0);
   return make_uint4(v[0], v[1], v[2], v[3]);
 }
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+__device__ __forceinline__ void buffer_store8(BufferRsrc r, uint32_t lane_off, uint32_t x, uint32_t y) {
+  const u32x2 v = {x, y};
+  __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)lane_off, 0, 0);
+}
+// Per lane: a where the lane's bit of the wave mask is set, else b (one v_cndmask on the mask).
+template <typename T>
+__device__ __forceinline__ T select_by_mask(unsigned long long mask, T a, T b) {
+  static_assert(sizeof(T) == 4, "32-bit values");
+  uint32_t r;
+  asm("v_cndmask_b32 %0, %1, %2, %3" : "=v"(r) : "v"((uint32_t)b), "v"((uint32_t)a), "s"(mask));
+  return (T)r;
+}
 __device__ __forceinline__ void buffer_store4(BufferRsrc r, uint32_t lane_off, uint32_t wave_off, float x) {
   __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(x), r, (int)lane_off, (int)wave_off, 0);
 }
@@ -350,20 +363,23 @@ constexpr int kKP = 17;  // 16-byte slots per key row in LDS: 16 of data + 1 of 
 constexpr int kKP8 = 9;  // the same for rows kept as fp8 codes: 8 of data + 1 of padding
 // Queries per sequence from which the tiled matrix-core kernel is used.
 constexpr int kTileMinQueries = 8;
-constexpr int kStageCap = 320;  // filter mode: staged candidates per wavefront and pair of queries
 
 // MODE kTileStore: scores of all keys go to S [rows, L].
 // MODE kTileSample: only one key of every group of kSampleStride consecutive
 //   keys is scored (at a hashed position inside its group); the result is a
 //   score matrix [rows, L / kSampleStride] in which a query sees the first
 //   n / kSampleStride entries.
-// MODE kTileFilter: nothing is stored densely; (key, score) pairs whose score
-//   reaches the row's threshold aux.tau are appended to the row's candidate
-//   list.  A wavefront owns its queries, so it collects their candidates in
-//   private LDS staging lists with ballot-computed slots (one list per pair of
-//   queries that share an accumulator slot in the two half-waves, entries tagged
-//   with the half) and moves them to the global lists in batches, one global
-//   atomic per query and batch.
+// MODE kTileFilter: nothing is stored densely; (key, score) pairs whose score reaches the row's
+//   threshold aux.tau go to the row's candidate list.  The list of a row is cut into one
+//   segment per key range (aux.seg: offsets [rows, ranges + 1], sized by the caller from the
+//   sampled scores of that range), and the workgroup of a (query tile, key range) is the only
+//   writer of its segments: a wavefront keeps the fill of its queries' segments in scalar
+//   registers, computes the slots of a column tile's hits from the ballot, and stores them
+//   straight to the list through a buffer descriptor - lanes without a hit, or past the end of
+//   the segment, store to an offset outside the descriptor's range, which drops the store, so
+//   there is no branch, no staging list and no atomic.  At the end the fills are written to
+//   aux.seg_count [rows, ranges] (a fill above the segment's length tells the caller that it
+//   overflowed).
 // The work of one workgroup: query tile q_tile of sequence blockIdx.z, key range blockIdx.x.
 template <int KDT, int HS, int MODE, bool PAGED, bool Q8>
 __device__ __forceinline__ void score_tile_body(
@@ -385,7 +401,6 @@ __device__ __forceinline__ void score_tile_body(
   __shared__ float kscl[2][kKT];
   __shared__ int nvis[QWG];
   __shared__ int s_head[QWG][HS];
-  __shared__ int2 stg[FILTER ? 4 * NQL_ * kStageCap : 1];
   __shared__ float s_tau[FILTER ? QWG : 1];  // thresholds of the workgroup's queries (+inf: no such query)
 
   const int LT = SAMPLE ? p.L / kSampleStride : p.L;  // keys in tile space
@@ -533,7 +548,14 @@ __device__ __forceinline__ void score_tile_body(
   // filter mode: thresholds of this lane's queries and the lengths of the wavefront's
   // staging lists (wavefront-uniform, so they live in scalar registers)
   float tauv[NQL];
-  int cnt[NQL], cnt_up[NQL];  // entries of a staging list; those of the upper half-wave's query among them
+  // fill of the list segments of the two queries in accumulator slot j (lower / upper half-wave):
+  // wavefront-uniform; this lane's segment: first element (relative to the first list of the
+  // query tile) and length
+  int cnt[NQL], cnt_up[NQL];
+  uint32_t seg_lo[NQL];
+  int seg_len[NQL];
+  const BufferRsrc crsrc = make_rsrc(FILTER ? static_cast<const void*>(aux.cand + ((size_t)seq * p.n_q + q_base) * aux.cap) : nullptr,
+                                     FILTER ? (uint32_t)QWG * (uint32_t)aux.cap * 8u : 0u);
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   int n_min = 0x7FFFFFFF;
 #pragma unroll
@@ -545,36 +567,30 @@ __device__ __forceinline__ void score_tile_body(
     cnt[j] = 0;
     cnt_up[j] = 0;
     tauv[j] = FILTER ? s_tau[qi] : 0.f;
-  }
-  // Moves staging list j (the candidates of the two queries in accumulator slot j of the
-  // lower and of the upper half-wave) to the global lists of those queries.
-  auto flush_list = [&](int j) {
-    const int c = cnt[j];
-    const int2* src = stg + (wave_u * NQL + j) * kStageCap;
-    // the totals of the two queries are kept while appending, so the atomics that reserve the
-    // room (one per query, lanes 0 and 1) go out first and the list is read while they travel
-    const int qi = wave_u * QW + (HS == 8 ? (j >> 1) * 4 + (lane & 1) * 2 + (j & 1) : (HS == 16 ? j * 2 + (lane & 1) : (lane & 1)));
-    const size_t my_row = (size_t)seq * p.n_q + q_base + qi;   // lanes 0 and 1: the two queries
-    int base = 0;
-    const int mine = lane == 0 ? c - cnt_up[j] : cnt_up[j];
-    if (lane < 2 && mine > 0) base = atomicAdd(&aux.count[my_row], mine);
-    int2 e = src[min(lane, c - 1)];
-    int run0 = __shfl(base, 0), run1 = __shfl(base, 1);
-    const long long row0 = __shfl((long long)my_row, 0), row1 = __shfl((long long)my_row, 1);
-    for (int i0 = 0; i0 < c; i0 += 64) {
-      const bool in = i0 + lane < c;
-      const bool up = in && e.x < 0, down = in && e.x >= 0;
-      const unsigned long long mu = __ballot(up), md = __ballot(down);
-      const int pos = up ? run1 + __popcll(mu & ((1ull << lane) - 1ull))
-                         : run0 + __popcll(md & ((1ull << lane) - 1ull));
-      e.x &= 0x7FFFFFFF;
-      if (in && pos < aux.cap) aux.cand[(up ? row1 : row0) * aux.cap + pos] = e;
-      run1 += __popcll(mu);
-      run0 += __popcll(md);
-      if (i0 + 64 < c) e = src[min(i0 + 64 + lane, c - 1)];
+    seg_lo[j] = 0;
+    seg_len[j] = 0;
+    if (FILTER && ok) {
+      const int* sg = aux.seg + ((size_t)seq * p.n_q + q_base + qi) * (aux.ranges + 1) + blockIdx.x;
+      const int lo = sg[0];
+      seg_lo[j] = (uint32_t)qi * (uint32_t)aux.cap + (uint32_t)lo;
+      seg_len[j] = sg[1] - lo;
     }
-    cnt[j] = 0;
-    cnt_up[j] = 0;
+  }
+  // Stores the hits of accumulator slot j named by the ballot m (score sc, key key of this
+  // lane) into the segments of its two queries and advances their fills.
+  const unsigned long long upper_half = 0xFFFFFFFF00000000ull;
+  auto append_hits = [&](int j, unsigned long long m, int key, float sc) {
+    const uint32_t m_lo = (uint32_t)m, m_hi = (uint32_t)(m >> 32);
+    const int n_lo = __popc(m_lo);
+    // slot = fill of the lane's own segment + hits of its half-wave below it (upper lanes see
+    // all n_lo lower hits in the running count, so their fill is entered less n_lo)
+    const int base = select_by_mask(upper_half, cnt_up[j] - n_lo, cnt[j] - cnt_up[j]);
+    const int slot = __builtin_amdgcn_mbcnt_hi(m_hi, __builtin_amdgcn_mbcnt_lo(m_lo, base));
+    const unsigned long long fits = __ballot(slot < seg_len[j]) & m;
+    const uint32_t off = select_by_mask(fits, (seg_lo[j] + (uint32_t)slot) << 3, 0xFFFFFFF8u);
+    buffer_store8(crsrc, off, (uint32_t)key, __float_as_uint(sc));
+    cnt[j] += n_lo + __popc(m_hi);      // (cnt: both halves, cnt_up: the upper one)
+    cnt_up[j] += __popc(m_hi);
   };
 
   for (int i = 0; i < QWG; ++i) n_min = min(n_min, q_base + i < p.n_q ? nvis[i] : -1);
@@ -639,13 +655,7 @@ __device__ __forceinline__ void score_tile_body(
 #pragma unroll
       for (int j = 0; j < NQL; ++j) {
         const bool pass = out[j] >= tauv[j] && (PLAIN || (key < k_end && key < qn[j]));
-        const unsigned long long m = __ballot(pass);
-        // list length + passing lanes below this one
-        const int slot = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, cnt[j]));
-        if (pass)
-          stg[(wave_u * NQL + j) * kStageCap + slot] = make_int2(key | (int)((uint32_t)hf << 31), __float_as_int(out[j]));
-        cnt[j] += __popcll(m);
-        cnt_up[j] += __popc((uint32_t)(m >> 32));
+        append_hits(j, __ballot(pass), key, out[j]);
       }
     } else if (PLAIN) {
 #pragma unroll
@@ -707,14 +717,7 @@ __device__ __forceinline__ void score_tile_body(
     pend_m[j] = 0;
     pend_out[j] = 0.f;
   }
-  auto append_pending = [&](int j) {
-    const unsigned long long m = pend_m[j];
-    const int slot = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, cnt[j]));
-    if ((m >> lane) & 1ull)
-      stg[(wave_u * NQL + j) * kStageCap + slot] = make_int2(pend_key | (int)((uint32_t)hf << 31), __float_as_int(pend_out[j]));
-    cnt[j] += __popcll(m);
-    cnt_up[j] += __popc((uint32_t)(m >> 32));
-  };
+  auto append_pending = [&](int j) { append_hits(j, pend_m[j], pend_key, pend_out[j]); };
   auto drain_pending = [&]() {
 #pragma unroll
     for (int j = 0; j < NQL; ++j) {
@@ -808,32 +811,25 @@ __device__ __forceinline__ void score_tile_body(
       if (FILTER) filter_step(tag, accB, (nb * 64 + 32) * KP, accA, k0 + kKT + col, scaleA);
       else tile_step(tag, accB, (nb * 64 + 32) * KP, accA, k0 + kKT + col, scaleA);
       if (KDT == MISA_FP8_E4M3) scaleB = kscl[nb][32 + col];
-      if (FILTER) {
-#pragma unroll
-        for (int q = 0; q < NQL; ++q)     // up to 2 kKT entries per list and iteration
-          if (cnt[q] > kStageCap - 2 * kKT) flush_list(q);
-      }
       MISA_TILE_STORE(nb ^ 1);
       __syncthreads();
     };
     // iteration j finishes columns of the tiles j and j + 1: unmasked when both are
     for (int j = 0; j < n_plain - 1; ++j) body(Yes{}, j);
     for (int j = max(n_plain - 1, 0); j < n_tiles - 1; ++j) body(No{}, j);
-    if (FILTER) {
-      // the last column tile is finished at once: its entries (up to kKT per list) come
-      // on top of what the steps have appended already
-      drain_pending();
-#pragma unroll
-      for (int q = 0; q < NQL; ++q)
-        if (cnt[q] > kStageCap - kKT) flush_list(q);
-    }
+    if (FILTER) drain_pending();   // the last column tile is finished at once, after the pending one
     const int k_last = k_begin + (n_tiles - 1) * kKT + 32 + col;
     if (n_plain == n_tiles) epilogue(Yes{}, accB, k_last, scaleB);
     else epilogue(No{}, accB, k_last, scaleB);
-    if (FILTER) {
+  }
+  if (FILTER) {
+    // fills of this key range's segments (zero when no key of the range is visible): lanes 0
+    // and 32 write those of the lower and the upper half-wave's queries
 #pragma unroll
-      for (int q = 0; q < NQL; ++q)
-        if (cnt[q] > 0) flush_list(q);
+    for (int j = 0; j < NQL; ++j) {
+      const int qi = wave * QW + (HS == 8 ? (j >> 1) * 4 + hf * 2 + (j & 1) : (HS == 16 ? j * 2 + hf : hf));
+      if (col == 0 && q_base + qi < p.n_q)
+        aux.seg_count[((size_t)seq * p.n_q + q_base + qi) * aux.ranges + blockIdx.x] = hf ? cnt_up[j] : cnt[j] - cnt_up[j];
     }
   }
 #undef MISA_TILE_LOAD
@@ -1075,6 +1071,18 @@ int tile_queries_per_wg(const Prob& p, bool routed, bool q8) {
   return hc <= 8 ? (q8 ? 64 : 32) : (hc <= 16 ? 16 : 8);
 }
 
+int tile_key_ranges(const Prob& p, bool routed, bool q8, int mode, int* keys_per_wg) {
+  const int qwg = tile_queries_per_wg(p, routed, q8 && mode == kTileStore);
+  const int q_tiles = (p.n_q + qwg - 1) / qwg;
+  const int lt = mode == kTileSample ? p.L / kSampleStride : p.L;  // keys in tile space
+  // Key ranges: a multiple of 8 (one set per XCD), enough workgroups to fill
+  // the chip several times, at least 1024 keys each.
+  int splits = 8;
+  while (splits < 64 && (long long)splits * q_tiles * p.n_seq < 2048 && lt / (splits * 2) >= 1024) splits *= 2;
+  *keys_per_wg = ((lt + splits - 1) / splits + kKT - 1) / kKT * kKT;
+  return (lt + *keys_per_wg - 1) / *keys_per_wg;
+}
+
 template <int KDT, int MODE, bool Q8>
 static hipError_t launch_tile(const Prob& p, const void* Q, const float* W, const int* heads,
                               const void* K, const float* kscale, float* S, const TileAux& aux,
@@ -1083,13 +1091,9 @@ static hipError_t launch_tile(const Prob& p, const void* Q, const float* W, cons
   const int hs = hc <= 8 ? 8 : (hc <= 16 ? 16 : (hc <= 32 ? 32 : 64));
   const int qwg = tile_queries_per_wg(p, heads != nullptr, Q8 && MODE == kTileStore);
   const int q_tiles = (p.n_q + qwg - 1) / qwg;
-  const int lt = MODE == kTileSample ? p.L / kSampleStride : p.L;  // keys in tile space
-  // Key ranges: a multiple of 8 (one set per XCD), enough workgroups to fill
-  // the chip several times, at least 1024 keys each.
-  int splits = 8;
-  while (splits < 64 && (long long)splits * q_tiles * p.n_seq < 2048 && lt / (splits * 2) >= 1024) splits *= 2;
-  int keys_per_wg = ((lt + splits - 1) / splits + kKT - 1) / kKT * kKT;
-  dim3 grid((lt + keys_per_wg - 1) / keys_per_wg, q_tiles, p.n_seq);
+  int keys_per_wg = 0;
+  const int ranges = tile_key_ranges(p, heads != nullptr, Q8, MODE, &keys_per_wg);
+  dim3 grid(ranges, q_tiles, p.n_seq);
   const uint16_t* q = static_cast<const uint16_t*>(Q);
   if (MODE == kTileStore && aux.run) {
     // about one resident set of workgroups, each striding over the query tiles

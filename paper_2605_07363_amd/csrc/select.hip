@@ -10,8 +10,11 @@
 //                overwhelming probability at least k of all scores reach tau
 //                while only about 16 r do.  Rows with few visible keys get
 //                tau = -inf (everything is a candidate).
-//   3. filter    The tile scoring kernel runs over all keys and appends the
-//                (key, score) pairs with score >= tau to per-row lists.
+//   3. filter    The tile scoring kernel runs over all keys and writes the
+//                (key, score) pairs with score >= tau to per-row lists.  A row's
+//                list is cut into one segment per key range of that launch,
+//                sized in step 2 from the range's own sampled scores, so every
+//                segment has exactly one writer and needs no atomics.
 //   4. select    Per row, the exact top-k of the list (ties: lower index) is
 //                chosen by radix select in LDS and written in ascending index
 //                order.  Since every score >= tau is in the list, the result
@@ -25,6 +28,7 @@
 //
 // Everything is stream-ordered device work: no host read-back, so the call can
 // be captured in a HIP graph.
+#include <algorithm>
 #include <cmath>
 
 #include "kernels.h"
@@ -42,11 +46,30 @@ static int sample_rank(int k) {
   return (int)std::ceil(mu + 6.0 * std::sqrt(mu) + 8.0);
 }
 
-// List capacity: expected 16 r candidates plus six standard deviations, in units of 256.
-static int list_capacity(int k) {
-  const double r = sample_rank(k);
-  const double c = kSampleStride * r * (1.0 + 6.0 / std::sqrt(r));
-  return ((int)std::ceil(c) + 255) / 256 * 256;
+// Length of the list segment of a key range in which c sampled scores reached the threshold.
+// Exactly one key of every group of 16 is sampled, so with n keys of the range at or above
+// the threshold the count of sampled ones has mean n / 16 and variance below n / 16; the
+// segment holds 16 c plus six standard deviations of 16 (c - n / 16) at n = 16 (c + 1), plus
+// room for a range none of whose ~200 hits was sampled (probability (15/16)^200 < 3e-6) and
+// for the unsampled tail group.  Device and host use the same integer formula.
+__host__ __device__ inline int segment_length(int c) {
+  int root = 0;                                     // ceil(sqrt(c + 1))
+  while (root * root < c + 1) ++root;
+  return kSampleStride * c + 6 * kSampleStride * root + 128;
+}
+
+// At most this many sampled scores may reach the threshold of a row (r do by construction,
+// more only through ties at the threshold value); rows with more are left to the repair pass.
+static int max_sample_hits(int k) { return sample_rank(k) + sample_rank(k) / 4 + 16; }
+
+// List capacity of a row: the segment lengths add up to at most this (the square roots are
+// largest when the sampled hits are spread evenly over the ranges), in units of 256.
+static int list_capacity(int k, int ranges) {
+  const int hits = max_sample_hits(k);
+  const int per = (hits + ranges - 1) / ranges;
+  long long c = 0;
+  for (int r = 0; r < ranges; ++r) c += segment_length(per) + 6 * kSampleStride;   // (+ one more root: the roots are rounded up)
+  return (int)((c + 255) / 256 * 256);
 }
 
 static size_t select_lds_bytes(const Prob& p) {
@@ -70,14 +93,20 @@ __device__ __forceinline__ float key_to_float(uint32_t key) {
 // k-th largest score lies (select_rows_kernel spreads its first digit over [tau, upper]).  The
 // first 16 samples of every thread (4096 per row) stay in registers for both digit passes, all
 // their loads in flight together; longer rows read the rest again in the second pass.  Also
-// clears the row's candidate count and repair flags.
+// clears the row's repair flags and lays out the row's candidate list: seg[row][r] is the offset
+// of the segment of key range r (seg[row][ranges] the total), its length segment_length(samples
+// of the range that reach tau), cut to the visible keys of the range.  A row whose sampled hits
+// exceed max_hits (ties at the threshold value) gets empty segments and so falls to the repair
+// pass.  A row all of whose visible keys fit the list keeps every key (tau = -inf, segments =
+// the visible keys of each range).
 constexpr int kThrThreads = 256;
 constexpr int kThrHeld = 16;
 __global__ __launch_bounds__(kThrThreads) void select_threshold_kernel(
-    Prob p, const float* __restrict__ Ss, int m, int r, int cap, int qwg, int q_tiles,
-    float* __restrict__ tau, uint32_t* __restrict__ upper, int* __restrict__ count,
-    int* __restrict__ row_flag, int* __restrict__ tile_flag) {
+    Prob p, const float* __restrict__ Ss, int m, int r, int cap, int keep_all, int qwg, int q_tiles, int ranges,
+    int keys_per_range, int max_hits, float* __restrict__ tau, uint32_t* __restrict__ upper,
+    int* __restrict__ seg, int* __restrict__ row_flag, int* __restrict__ tile_flag) {
   __shared__ int hist[kBins];
+  __shared__ int range_hits[64];
   __shared__ int hist2[kBins];
   __shared__ int scan_scratch[32];
   __shared__ int thr[3];
@@ -87,15 +116,17 @@ __global__ __launch_bounds__(kThrThreads) void select_threshold_kernel(
   const int seq = row / p.n_q, t = row % p.n_q;
   const int n = visible(p, seq, t);
   if (tid == 0) {
-    count[row] = 0;
     row_flag[row] = 0;
     if (t % qwg == 0) tile_flag[seq * q_tiles + t / qwg] = 0;
   }
-  if (n <= cap) {  // every visible key fits into the list
+  int* row_seg = seg + (size_t)row * (ranges + 1);
+  if (n <= keep_all) {  // every visible key fits into the list (and into the registers of the row
+                        // selection): a range's segment holds its visible keys
     if (tid == 0) { tau[row] = -INFINITY; upper[row] = 0xFFFFFFFFu; }
+    if (tid <= ranges) row_seg[tid] = (int)min((long long)n, (long long)tid * keys_per_range);
     return;
   }
-  const int ns = n / kSampleStride;  // visible samples; ns > cap / 16 >= r
+  const int ns = n / kSampleStride;  // visible samples; ns > keep_all / 16 >= r
   const float* s = Ss + (size_t)row * m;
   float held[kThrHeld];
 #pragma unroll
@@ -131,9 +162,37 @@ __global__ __launch_bounds__(kThrThreads) void select_threshold_kernel(
   });
   __syncthreads();
   find_threshold_bin_n<kThrThreads>(hist2, need, scan_scratch, thr);
+  const float tau_row = key_to_float((d1 << 21) | ((uint32_t)thr[0] << 10));
   if (tid == 0) {
-    tau[row] = key_to_float((d1 << 21) | ((uint32_t)thr[0] << 10));
+    tau[row] = tau_row;
     upper[row] = ((uint32_t)thr_up[0] << 21) | 0x1FFFFFu;
+  }
+  // sampled scores of every key range that reach the threshold (sample i stands for the keys
+  // 16 i .. 16 i + 15, and a range is a whole number of such groups)
+  if (tid < 64) range_hits[tid] = 0;
+  __syncthreads();
+  const int groups_per_range = keys_per_range / kSampleStride;
+  auto tally = [&](float v, int i) {
+    if (v >= tau_row) atomicAdd(&range_hits[i / groups_per_range], 1);
+  };
+#pragma unroll
+  for (int u = 0; u < kThrHeld; ++u)
+    if (u * kThrThreads + tid < ns) tally(held[u], u * kThrThreads + tid);
+  for (int i = kThrHeld * kThrThreads + tid; i < ns; i += kThrThreads) tally(s[i], i);
+  __syncthreads();
+  if (tid < 64) {  // one wavefront: segment lengths, their prefix sums
+    const int hits = tid < ranges ? range_hits[tid] : 0;
+    int total_hits = hits;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) total_hits += __shfl_xor(total_hits, o);
+    const long long first_key = (long long)tid * keys_per_range;
+    const int visible_here = (int)max(0ll, min((long long)n - first_key, (long long)keys_per_range));
+    int len = tid < ranges ? min(segment_length(hits), visible_here) : 0;
+    if (total_hits > max_hits) len = 0;          // ties at the threshold: the repair pass takes the row
+    int end = wave_inclusive_scan(len);
+    if (__shfl(end, 63) > cap) { len = 0; end = 0; }   // cannot happen below max_hits; never lay out past the list
+    if (tid < ranges) row_seg[tid] = end - len;
+    if (tid == ranges - 1) row_seg[ranges] = end;
   }
 }
 
@@ -144,8 +203,8 @@ __global__ __launch_bounds__(kThrThreads) void select_threshold_kernel(
 // several rows share a compute unit.
 template <int NT, int EPT>
 __global__ __launch_bounds__(NT) void select_rows_kernel(
-    Prob p, const int2* __restrict__ cand, const int* __restrict__ count,
-    const float* __restrict__ tau, const uint32_t* __restrict__ upper, int cap, int k, int qwg,
+    Prob p, const int2* __restrict__ cand, const int* __restrict__ seg, const int* __restrict__ seg_count,
+    int ranges, const float* __restrict__ tau, const uint32_t* __restrict__ upper, int cap, int k, int qwg,
     int q_tiles, int* __restrict__ idx, float* __restrict__ val, int* __restrict__ row_flag,
     int* __restrict__ tile_flag) {
   extern __shared__ uint32_t dyn[];  // selection bitmap, then the prefix count of every bitmap word
@@ -155,6 +214,9 @@ __global__ __launch_bounds__(NT) void select_rows_kernel(
   __shared__ uint32_t bkey[64];
   __shared__ int bidx[64];
   __shared__ int b_len;
+  __shared__ int seg_first[65];   // offset of a range's segment in the row's list
+  __shared__ int seg_pre[65];     // entries of the ranges before it (compact numbering of the row's entries)
+  __shared__ int seg_bad;
   const int t = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
   const size_t row = (size_t)seq * p.n_q + t;
   const int n = visible(p, seq, t);
@@ -166,8 +228,24 @@ __global__ __launch_bounds__(NT) void select_rows_kernel(
     if (out_val) out_val[i] = -INFINITY;
   }
   if (k_eff == 0) return;
-  const int c = count[row];
-  if (c > cap || c < k_eff) {  // list overflowed or threshold too high: leave the row to the repair pass
+  // the row's entries: range r holds seg_count[r] of them from seg[r] on; a count above the
+  // segment's length means that hits were dropped
+  if (tid < 64) {
+    int cnt = 0, len = 0, first = 0;
+    if (tid < ranges) {
+      first = seg[row * (ranges + 1) + tid];
+      len = seg[row * (ranges + 1) + tid + 1] - first;
+      cnt = seg_count[row * ranges + tid];
+    }
+    const unsigned long long bad = __ballot(cnt > len);
+    const int end = wave_inclusive_scan(cnt);
+    seg_first[tid] = first;
+    seg_pre[tid] = end - cnt;
+    if (tid == 63) { seg_pre[64] = end; seg_bad = bad != 0; }
+  }
+  __syncthreads();
+  const int c = seg_pre[64];
+  if (seg_bad || c > NT * EPT || c < k_eff) {  // a segment overflowed, more entries than this kernel holds, or threshold too high: leave the row to the repair pass
     if (tid == 0) {
       row_flag[row] = 1;
       tile_flag[seq * q_tiles + t / qwg] = 1;
@@ -182,11 +260,19 @@ __global__ __launch_bounds__(NT) void select_rows_kernel(
   uint32_t ek[EPT];
   float ev[EPT];
   const int2* src = cand + row * (size_t)cap;
+  int rg = 0, rg_begin = 0, rg_end = seg_pre[1];   // the range whose entries [rg_begin, rg_end) hold entry i
 #pragma unroll
   for (int u = 0; u < EPT; ++u) {
-    const int i = tid + u * NT;
+    const int i = tid + u * NT;                    // (increasing with u: the range only moves forward)
     int2 e = make_int2(-1, 0);
-    if (i < c) e = src[i];
+    if (i < c) {
+      while (rg_end <= i) {                        // ends at the latest at range 63: seg_pre[64] = c > i
+        ++rg;
+        rg_begin = rg_end;
+        rg_end = seg_pre[rg + 1];
+      }
+      e = src[seg_first[rg] + (i - rg_begin)];
+    }
     ei[u] = e.x;
     ev[u] = __int_as_float(e.y);
     ek[u] = order_key(ev[u]);
@@ -354,8 +440,8 @@ __global__ __launch_bounds__(NT) void select_rows_kernel(
 namespace {
 
 struct Layout {
-  size_t S, sample, tau, upper, count, row_flag, tile_flag, cand, total;
-  int m, cap, qwg, q_tiles;
+  size_t S, sample, tau, upper, row_flag, tile_flag, seg, seg_count, cand, total;
+  int m, cap, qwg, q_tiles, ranges, keys_per_range;
 };
 
 size_t up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -364,7 +450,8 @@ Layout layout(const Prob& p, bool routed, int k, bool q8 = false) {
   Layout l;
   const size_t rows = (size_t)p.n_seq * p.n_q;
   l.m = p.L / kSampleStride;
-  l.cap = list_capacity(k);
+  l.ranges = tile_key_ranges(p, routed, q8, kTileFilter, &l.keys_per_range);
+  l.cap = list_capacity(k, l.ranges);
   l.qwg = tile_queries_per_wg(p, routed, q8);
   l.q_tiles = (p.n_q + l.qwg - 1) / l.qwg;
   size_t o = 0;
@@ -372,9 +459,10 @@ Layout layout(const Prob& p, bool routed, int k, bool q8 = false) {
   l.sample = o;    o += up(rows * l.m * sizeof(float));
   l.tau = o;       o += up(rows * sizeof(float));
   l.upper = o;     o += up(rows * sizeof(uint32_t));
-  l.count = o;     o += up(rows * sizeof(int));
   l.row_flag = o;  o += up(rows * sizeof(int));
   l.tile_flag = o; o += up((size_t)p.n_seq * l.q_tiles * sizeof(int));
+  l.seg = o;       o += up(rows * (l.ranges + 1) * sizeof(int));
+  l.seg_count = o; o += up(rows * l.ranges * sizeof(int));
   l.cand = o;      o += up(rows * l.cap * sizeof(int2));
   l.total = o;
   return l;
@@ -386,8 +474,9 @@ size_t select_ws_bytes(const Prob& p, int k_dtype, int q_dtype, int k) {
   if (k < 1) return 0;
   const size_t dense = up((size_t)p.n_seq * p.n_q * p.L * sizeof(float));
   if (!fused(p, k_dtype, q_dtype, k)) return dense + up(topk_ws_bytes(p, k));
-  // the larger head count (unrouted call) gives the smaller query tiles, hence more flags
-  return layout(p, false, k).total;
+  // the number of key ranges, hence the list capacity, and the number of query tiles depend
+  // on the head count of the call: room for either kind
+  return std::max(layout(p, false, k).total, layout(p, true, k).total);
 }
 
 long long select_row_flags_offset(const Prob& p, int k_dtype, int q_dtype, bool routed, int k) {
@@ -411,23 +500,34 @@ hipError_t launch_select(const Prob& p, int k_dtype, int q_dtype, const void* Q,
   float* Ss = reinterpret_cast<float*>(base + l.sample);
   float* tau = reinterpret_cast<float*>(base + l.tau);
   uint32_t* upper = reinterpret_cast<uint32_t*>(base + l.upper);
-  int* count = reinterpret_cast<int*>(base + l.count);
+  int* seg = reinterpret_cast<int*>(base + l.seg);
+  int* seg_count = reinterpret_cast<int*>(base + l.seg_count);
   int* row_flag = reinterpret_cast<int*>(base + l.row_flag);
   int* tile_flag = reinterpret_cast<int*>(base + l.tile_flag);
   int2* cand = reinterpret_cast<int2*>(base + l.cand);
   const dim3 rows(p.n_q, p.n_seq);
 
+  // the row selection holds a row's entries in registers: 512 threads x 10 for up to 5120
+  // expected entries (16 r plus six standard deviations), 1024 x 13 above (measured on MI355X);
+  // rows with more entries go to the repair pass
+  const double rr = sample_rank(k);
+  const bool small_rows = kSampleStride * rr * (1.0 + 6.0 / std::sqrt(rr)) <= 5120.0;
+  const int entry_limit = small_rows ? 512 * 10 : 1024 * 13;   // k = kFusedMaxK: 13056 expected
+
   hipError_t e = launch_tile_mode(p, k_dtype, q_dtype, kTileSample, TileAux{}, Q, W, heads, K, kscale, Ss, st);
   if (e != hipSuccess) return e;
   select_threshold_kernel<<<p.n_seq * p.n_q, kThrThreads, 0, st>>>(
-      p, Ss, l.m, sample_rank(k), l.cap, l.qwg, l.q_tiles, tau, upper, count, row_flag, tile_flag);
+      p, Ss, l.m, sample_rank(k), l.cap, std::min(l.cap, entry_limit), l.qwg, l.q_tiles, l.ranges, l.keys_per_range, max_sample_hits(k), tau,
+      upper, seg, row_flag, tile_flag);
   if ((e = hipGetLastError()) != hipSuccess) return e;
 
   TileAux filter;
   filter.tau = tau;
   filter.cand = cand;
-  filter.count = count;
+  filter.seg = seg;
+  filter.seg_count = seg_count;
   filter.cap = l.cap;
+  filter.ranges = l.ranges;
   e = launch_tile_mode(p, k_dtype, q_dtype, kTileFilter, filter, Q, W, heads, K, kscale, nullptr, st);
   if (e != hipSuccess) return e;
 
@@ -437,13 +537,11 @@ hipError_t launch_select(const Prob& p, int k_dtype, int q_dtype, const void* Q,
     static LdsSeen seen;                                                                            \
     e = ensure_dynamic_lds(reinterpret_cast<const void*>(select_rows_kernel<NT, EPT>), lds, seen);  \
     if (e != hipSuccess) return e;                                                                  \
-    select_rows_kernel<NT, EPT><<<rows, NT, lds, st>>>(p, cand, count, tau, upper, l.cap, k, l.qwg, \
-                                                       l.q_tiles, idx, val, row_flag, tile_flag);   \
+    select_rows_kernel<NT, EPT><<<rows, NT, lds, st>>>(p, cand, seg, seg_count, l.ranges, tau, upper, l.cap, k, \
+                                                       l.qwg, l.q_tiles, idx, val, row_flag, tile_flag); \
   } while (0)
-  // thread count per row by list size (measured on MI355X: 512 for lists up to 5120
-  // entries, 1024 above)
-  if (l.cap <= 5120) GO(512, 10);
-  else GO(1024, 13);  // list_capacity(kFusedMaxK) = 13056 <= 13 * 1024
+  if (small_rows) GO(512, 10);
+  else GO(1024, 13);
 #undef GO
   if ((e = hipGetLastError()) != hipSuccess) return e;
 

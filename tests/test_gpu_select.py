@@ -115,6 +115,39 @@ def test_select_matches_oracle_and_two_call_path(misa, name):
     check_against_oracle(inp, heads, idx, val, wl.k, [rows[i] for i in pick])
 
 
+@pytest.mark.parametrize("where", ["one_range", "range_edges", "every_other_range"])
+def test_select_with_hits_concentrated_in_few_key_ranges(misa, where):
+    # The candidate list of a row is cut into one segment per key range, sized from the sampled
+    # scores of that range.  Here all gates are positive and the keys of a few stretches are eight
+    # times larger than the rest, so nearly all scores above the threshold fall into one range,
+    # into the first and last keys of every range, or into every other range; the segments must
+    # adapt (no row may need the repair pass) and the result must equal the two calls bit for bit.
+    wl = small("c2", L=32768, n_q=40, k=1024)
+    inp = WL.make_inputs(wl, seed=21)
+    K = O.bf16_bits_to_f64(inp["K"]).astype(np.float32)
+    boost = np.ones(wl.L, dtype=np.float32)
+    if where == "one_range":
+        boost[9000:11500] = 8.0
+    elif where == "range_edges":
+        for start in range(0, wl.L, 2048):
+            boost[start:start + 70] = 8.0
+            boost[start + 2048 - 70:start + 2048] = 8.0
+    else:
+        for start in range(0, wl.L, 4096):
+            boost[start:start + 2048] = 8.0
+    inp["K"] = WL.f32_to_bf16_bits(K * boost[None, :, None])
+    inp["W"] = np.abs(inp["W"]) + 0.01
+    dv = misa.to_device(inp)
+    p = dv["problem"]
+    heads = random_heads(wl)
+    idx, val = one_call(misa, p, dv, heads, wl.k)
+    ref_idx, ref_val = two_call(misa, p, dv, heads, wl.k)
+    assert torch.equal(idx, ref_idx)
+    assert torch.equal(val, ref_val)
+    assert int(one_call.repaired.sum()) == 0
+    check_against_oracle(inp, heads, idx, val, wl.k, [(0, 0), (0, 39)])
+
+
 def test_select_rows_of_every_length(misa):
     # Causal queries from the very first position on, and ragged sequences: rows with no visible key,
     # fewer than k, few enough to keep every key, and long ones, in the same call.

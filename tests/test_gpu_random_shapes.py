@@ -106,3 +106,12 @@ def test_random_problem_fused_call_equals_two_calls(misa, seed):
         d.score(dv["Q"], dv["W"], dv["K"], dv["kscale"])
         d.select()
         assert torch.equal(d.idx, ia) and torch.equal(d.S, a.S)
+    if wl.q_dtype == "e4m3" and wl.k_dtype == "e4m3":
+        # the same on the fp8 matrix instruction: fused call = two calls bit for bit there too
+        from dataclasses import replace
+        pm = replace(p, q_dtype=misa.FP8_E4M3_MATRIX)
+        e = misa.Indexer(pm, wl.k, want_val=True)
+        f = misa.Indexer(pm, wl.k, want_val=True, fused=True)
+        ie = e.run(dv["K"], dv["kscale"], dv["Q"], dv["W"])
+        jf = f.run(dv["K"], dv["kscale"], dv["Q"], dv["W"])
+        assert torch.equal(ie, jf) and torch.equal(e.val, f.val)

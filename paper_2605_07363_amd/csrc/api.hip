@@ -382,6 +382,10 @@ misa_status misa_rerank(const misa_problem* p, const void* Q, const float* W, co
   // the candidate gather takes fp8 codes with fp8 keys for any number of queries
   const bool native = p->q_dtype == MISA_FP8_E4M3_MATRIX && p->k_dtype == MISA_FP8_E4M3;
   if ((st = stage_queries(p, Q, ws_bytes_for(pr, MISA_OP_RERANK, k_cand), ws, ws_bytes, stream, &qv, native)) != MISA_OK) return st;
+  if (misa::rerank_fused_path(pr, p->k_dtype, qv.q_dtype, k_cand))
+    return hip_result(misa::launch_rerank_fused(pr, p->k_dtype, qv.q_dtype, qv.Q, W, K, kscale, cand, k_cand, k,
+                                                idx, val, (hipStream_t)stream),
+                      "misa_rerank launch");
   float* dense = static_cast<float*>(qv.ws);
   hipError_t e = misa::launch_score(pr, p->k_dtype, qv.q_dtype, qv.Q, W, nullptr, K, kscale, cand, k_cand,
                                     dense, (hipStream_t)stream);

@@ -30,6 +30,16 @@ hipError_t launch_score(const Prob& p, int k_dtype, int q_dtype, const void* Q, 
                         const int* heads, const void* K, const float* kscale, const int* cand,
                         int k_cand, float* out, hipStream_t st);
 
+// The whole re-rank of a query (dense scores of its k_cand candidates, Eq. dsa_score, and their
+// top-k, Eq. misa_final_topk) in one workgroup, no score matrix: taken when rerank_fused_path says
+// so (at least kRerankFusedMinRows queries, k_cand <= 8192, matrix-core types); the results equal
+// launch_score + launch_topk(map = cand) bit for bit.
+constexpr int kRerankFusedMinRows = 1024;
+bool rerank_fused_path(const Prob& p, int k_dtype, int q_dtype, int k_cand);
+hipError_t launch_rerank_fused(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,
+                               const void* K, const float* kscale, const int* cand, int k_cand, int k,
+                               int* idx, float* val, hipStream_t st);
+
 // The prefill (matrix-core tile) scoring kernel in its three modes; see score.hip.
 enum { kTileStore = 0, kTileSample = 1, kTileFilter = 2 };
 constexpr int kSampleStride = 16;

@@ -21,6 +21,7 @@
 #include <type_traits>
 
 #include "kernels.h"
+#include "small_topk.h"
 
 namespace misa {
 
@@ -881,13 +882,18 @@ __global__ __launch_bounds__(256) void score_tile_repair_kernel(
 // candidate indices) costs about a fifth of the kernel with 2048 candidates each, so many-query
 // problems take 4096 (0.37 ms against 0.39 ms on the 2048 x 8192 re-rank); few-query problems
 // take shorter pieces to put more workgroups on the chip.
+// FUSED (the whole re-rank of a query in one workgroup, Eq. misa_final_topk): the workgroup takes
+// all k' <= 8192 candidates, the scores replace the candidate indices in LDS as they are
+// produced (a slot's index has been consumed by then) and the row's top-k is taken from there by
+// small_row_topk - no dense score matrix, no second launch.
 constexpr int kGatherChunk = 4096;
 
-template <int KDT, int RT, bool Q8>
+template <int KDT, int RT, bool Q8, bool FUSED>
 __global__ __launch_bounds__(256) void score_gather_kernel(
     Prob p, const uint16_t* __restrict__ Q, const float* __restrict__ W,
     const void* __restrict__ K, const float* __restrict__ kscale, const int* __restrict__ cand,
-    int k_cand, int chunk, float* __restrict__ out) {
+    int k_cand, int chunk, float* __restrict__ out, int k, int* __restrict__ idx,
+    float* __restrict__ val) {
   constexpr int ROW_BYTES = KDT == MISA_BF16 ? 256 : 128;
   constexpr int NLD = KDT == MISA_BF16 ? 8 : 4;  // 16-byte loads per lane and key (half a row)
   const int t = blockIdx.y, seq = blockIdx.z;
@@ -902,7 +908,7 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
 
   // The candidate indices of this workgroup go through LDS, so that reading them
   // in the loop does not wait on the key loads in flight.
-  __shared__ int s_cand[kGatherChunk];
+  __shared__ int s_cand[FUSED ? kSmallTopkMax : kGatherChunk];
   for (int i = threadIdx.x; i < chunk; i += 256) s_cand[i] = c_begin + i < c_end ? crow[c_begin + i] : -1;
 
   // Row m of tile rt is head rt*32 + m; half-wave hf holds components 64 hf .. 64 hf + 63,
@@ -996,27 +1002,39 @@ __global__ __launch_bounds__(256) void score_gather_kernel(
       for (int q = 0; q < 16; ++q) sum = fmaf(s_gate[hf][rt * 16 + q], relu(acc[rt][q]), sum);
     sum += __shfl_xor(sum, 32);
     const int slot = c0 + col;
-    if (hf == 0 && slot < c_end) orow[slot] = r.s >= 0 ? sum * r.scale : -INFINITY;
+    if (hf == 0 && slot < c_end) {
+      const float score = r.s >= 0 ? sum * r.scale : -INFINITY;
+      if (FUSED) s_cand[slot] = __float_as_int(score);   // (c_begin = 0; this slot's index was read at issue)
+      else orow[slot] = score;
+    }
   };
 
   // kDepth register buffers: the loads of a step are issued kDepth - 1 steps before they are
   // used (a step of one wavefront is far shorter than the latency of a gathered row).
   constexpr int kDepth = 2;
-  Raw buf[kDepth];
-  int c0 = c_begin + wave * 32;
   __builtin_amdgcn_s_waitcnt(0);  // the query operand has landed; in-loop waits concern only loop loads
   __syncthreads();                // candidate indices are in LDS
+  auto stream_candidates = [&]() {
+    Raw buf[kDepth];
+    int c0 = c_begin + wave * 32;
 #pragma unroll
-  for (int d = 0; d < kDepth - 1; ++d) issue(buf[d], c0 + 128 * d);
-  while (true) {
+    for (int d = 0; d < kDepth - 1; ++d) issue(buf[d], c0 + 128 * d);
+    while (true) {
 #pragma unroll
-    for (int d = 0; d < kDepth; ++d) {
-      issue(buf[(d + kDepth - 1) % kDepth], c0 + 128 * (kDepth - 1));
-      __builtin_amdgcn_sched_barrier(0);
-      finish(buf[d], c0);
-      c0 += 128;
-      if (c0 >= c_end) return;
+      for (int d = 0; d < kDepth; ++d) {
+        issue(buf[(d + kDepth - 1) % kDepth], c0 + 128 * (kDepth - 1));
+        __builtin_amdgcn_sched_barrier(0);
+        finish(buf[d], c0);
+        c0 += 128;
+        if (c0 >= c_end) return;
+      }
     }
+  };
+  stream_candidates();
+  if constexpr (FUSED) {
+    __shared__ SmallTopkLds topk_lds;
+    __syncthreads();                // all scores of the row are in LDS
+    small_row_topk(s_cand, k_cand, k, crow, idx + qrow * k, val ? val + qrow * k : nullptr, topk_lds);
   }
 }
 
@@ -1162,10 +1180,42 @@ static hipError_t launch_gather(const Prob& p, const void* Q, const float* W, co
   const dim3 grid((k_cand + chunk - 1) / chunk, p.n_q, p.n_seq);
   const uint16_t* q = static_cast<const uint16_t*>(Q);
   if (p.H <= 32)
-    score_gather_kernel<KDT, 1, Q8><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, chunk, out);
+    score_gather_kernel<KDT, 1, Q8, false><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, chunk, out, 0, nullptr, nullptr);
   else
-    score_gather_kernel<KDT, 2, Q8><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, chunk, out);
+    score_gather_kernel<KDT, 2, Q8, false><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, chunk, out, 0, nullptr, nullptr);
   return hipGetLastError();
+}
+
+// Re-rank with the top-k inside the gather kernel: for many queries with short candidate lists
+// (one workgroup per query fills the chip, the list fits LDS) and the types the gather kernel
+// takes.
+bool rerank_fused_path(const Prob& p, int k_dtype, int q_dtype, int k_cand) {
+  const bool types = (q_dtype == MISA_BF16 && k_dtype != MISA_F32) ||
+                     (q_dtype == MISA_FP8_E4M3 && k_dtype == MISA_FP8_E4M3);
+  return types && k_cand <= kSmallTopkMax && (long long)p.n_q * p.n_seq >= kRerankFusedMinRows;
+}
+
+template <int KDT, bool Q8>
+static hipError_t launch_gather_topk(const Prob& p, const void* Q, const float* W, const void* K,
+                                     const float* kscale, const int* cand, int k_cand, int k, int* idx,
+                                     float* val, hipStream_t st) {
+  const int chunk = (k_cand + 127) / 128 * 128;
+  const dim3 grid(1, p.n_q, p.n_seq);
+  const uint16_t* q = static_cast<const uint16_t*>(Q);
+  if (p.H <= 32)
+    score_gather_kernel<KDT, 1, Q8, true><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, chunk, nullptr, k, idx, val);
+  else
+    score_gather_kernel<KDT, 2, Q8, true><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, chunk, nullptr, k, idx, val);
+  return hipGetLastError();
+}
+
+hipError_t launch_rerank_fused(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,
+                               const void* K, const float* kscale, const int* cand, int k_cand, int k,
+                               int* idx, float* val, hipStream_t st) {
+  if (!rerank_fused_path(p, k_dtype, q_dtype, k_cand)) return hipErrorInvalidValue;
+  if (q_dtype == MISA_FP8_E4M3) return launch_gather_topk<MISA_FP8_E4M3, true>(p, Q, W, K, kscale, cand, k_cand, k, idx, val, st);
+  if (k_dtype == MISA_BF16) return launch_gather_topk<MISA_BF16, false>(p, Q, W, K, kscale, cand, k_cand, k, idx, val, st);
+  return launch_gather_topk<MISA_FP8_E4M3, false>(p, Q, W, K, kscale, cand, k_cand, k, idx, val, st);
 }
 
 hipError_t launch_score(const Prob& p, int k_dtype, int q_dtype, const void* Q, const float* W,

@@ -1,0 +1,177 @@
+"""Re-rank of many queries with short candidate lists (Eq. misa_final_topk on Eq. dsa_score of
+the candidates): the library takes the dense scores and their top-k in one kernel there.  Checked
+against the oracle and, bit for bit, against the same rows re-ranked as sub-problems too small
+for that kernel (dense scores through the workspace, then the row top-k)."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import misa_oracle as O
+from paper_2605_07363_amd import workloads as WL
+from helpers import ABS_FRAC, ABS_FRAC_FP8_MATRIX, assert_scores_close, check_index_set, oracle_view
+
+pytestmark = pytest.mark.gpu
+
+@pytest.fixture(scope="module")
+def misa():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2605_07363_amd import misa as m
+    return m
+
+
+ROWS = 1100          # above the library's threshold for the one-kernel path (1024 rows)
+
+
+def _problem(seed, k_dtype, q_dtype, H, L):
+    wl = WL.scaled(WL.WORKLOADS["c2"], n_seq=1, L=L, n_q=ROWS, H=H, h=1, B=64, k=1, k_cand=0,
+                   k_dtype=k_dtype, q_dtype=q_dtype, needles=6, name=f"rrf{seed}")
+    return wl, WL.make_inputs(wl, seed=seed)
+
+
+def _candidates(rng, rows, L, kc, full=False):
+    cand = np.full((1, rows, kc), -1, dtype=np.int32)
+    for t in range(rows):
+        m = kc if full else int(rng.integers(0, kc + 1))
+        c = np.sort(rng.choice(L, size=min(m, L), replace=False)).astype(np.int32)
+        if not full:
+            c[rng.random(c.shape[0]) < 0.03] = -1                 # holes
+        cand[0, t, :c.shape[0]] = c
+    return cand
+
+
+def _rerank(misa, p, dv, cand, kc, k, Q=None):
+    rows = p.n_q
+    idx = torch.full((1, rows, k), -9, dtype=torch.int32, device="cuda")
+    val = torch.full((1, rows, k), 7.0, dtype=torch.float32, device="cuda")
+    misa.rerank(p, dv["Q"] if Q is None else Q, dv["W"], dv["K"], dv["kscale"], cand, kc, k, idx, val,
+                misa.alloc_workspace(p, misa.OP_RERANK, kc))
+    torch.cuda.synchronize()
+    return idx, val
+
+
+def _rerank_in_pieces(misa, p, dv, cand, kc, k, piece=500):
+    """The same rows as sub-problems of `piece` queries: below the one-kernel threshold."""
+    idx, val = [], []
+    for a in range(0, p.n_q, piece):
+        b = min(a + piece, p.n_q)
+        pp = replace(p, n_q=b - a, q_pos=p.q_pos[a:b].contiguous())
+        part = dict(dv, Q=dv["Q"][:, a:b].contiguous(), W=dv["W"][:, a:b].contiguous())
+        i, v = _rerank(misa, pp, part, cand[:, a:b].contiguous(), kc, k)
+        idx.append(i); val.append(v)
+    return torch.cat(idx, dim=1), torch.cat(val, dim=1)
+
+
+def _check_rows_against_oracle(inp, cand, idx, val, k, rows, what, abs_frac=ABS_FRAC):
+    for t in rows:
+        K, q, w, n = oracle_view(inp, 0, t)
+        dense = O.dsa_scores(q, w, K, n) if n else np.zeros(0)
+        valid = np.array(sorted(c for c in cand[0, t] if 0 <= c < n), dtype=np.int64)
+        ke = min(k, valid.shape[0])
+        got = idx[0, t]
+        assert np.all(got[ke:] == -1) and np.all(np.diff(got[:ke]) > 0), f"{what} row {t}"
+        assert set(got[:ke].tolist()) <= set(valid.tolist()), f"{what} row {t}"
+        pos = np.searchsorted(valid, got[:ke])
+        padded = np.concatenate([pos, np.full(k - ke, -1, dtype=pos.dtype)])
+        check_index_set(padded, dense[valid], k, f"{what} row {t}", abs_frac=abs_frac)
+        assert_scores_close(val[0, t, :ke], dense[got[:ke]], f"{what} values row {t}", abs_frac=abs_frac)
+        assert np.all(np.isneginf(val[0, t, ke:]))
+
+
+@pytest.mark.parametrize("k_dtype,q_dtype,H,kc,k", [
+    ("bf16", "bf16", 64, 700, 100),      # list length not a multiple of the 128-candidate step
+    ("e4m3", "bf16", 64, 1024, 1024),    # k = k': everything that is valid is kept
+    ("e4m3", "bf16", 17, 333, 50),       # one row tile, odd head count
+    ("bf16", "bf16", 32, 2500, 640),
+])
+def test_many_query_rerank_against_the_oracle(misa, k_dtype, q_dtype, H, kc, k):
+    seed = 9900 + kc
+    rng = np.random.default_rng(seed)
+    L = 3000
+    wl, inp = _problem(seed, k_dtype, q_dtype, H, L)
+    dv = misa.to_device(inp)
+    p = dv["problem"]
+    cand = _candidates(rng, ROWS, L, kc)
+    cand[0, 5, kc // 2] = L + 7                           # beyond the cache: skipped
+    dcand = torch.from_numpy(cand).cuda()
+    idx, val = _rerank(misa, p, dv, dcand, kc, k)
+    sample = [0, 1, 5, ROWS - 1] + rng.choice(ROWS, size=36, replace=False).tolist()
+    _check_rows_against_oracle(inp, cand, idx.cpu().numpy(), val.cpu().numpy(), k, sample, f"fused rerank {k_dtype}")
+    # all rows, bit for bit, against the path that keeps the dense scores
+    idx2, val2 = _rerank_in_pieces(misa, p, dv, dcand, kc, k)
+    assert torch.equal(idx, idx2)
+    assert torch.equal(val, val2)
+
+
+def test_many_query_rerank_on_the_fp8_matrix_instruction(misa):
+    if not misa.HAS_FP8_MFMA:
+        pytest.skip("library built without the fp8 matrix path")
+    seed, L, kc, k = 9931, 3000, 900, 128
+    rng = np.random.default_rng(seed)
+    wl, inp = _problem(seed, "e4m3", "e4m3", 64, L)
+    dv = misa.to_device(inp)
+    p = replace(dv["problem"], q_dtype=misa.FP8_E4M3_MATRIX)
+    cand = _candidates(rng, ROWS, L, kc)
+    dcand = torch.from_numpy(cand).cuda()
+    idx, val = _rerank(misa, p, dv, dcand, kc, k)
+    sample = [0, ROWS - 1] + rng.choice(ROWS, size=30, replace=False).tolist()
+    _check_rows_against_oracle(inp, cand, idx.cpu().numpy(), val.cpu().numpy(), k, sample, "fused rerank fp8 x fp8",
+                               abs_frac=ABS_FRAC_FP8_MATRIX)
+    idx2, val2 = _rerank_in_pieces(misa, p, dv, dcand, kc, k)
+    assert torch.equal(idx, idx2)
+    assert torch.equal(val, val2)
+
+
+def _times_power_of_two(bits, e):
+    """bf16 bit patterns of normal numbers multiplied by 2^e."""
+    return (bits.astype(np.int32) + (e << 7)).astype(bits.dtype)
+
+
+@pytest.mark.parametrize("shape", ["constant", "three_values", "outliers", "tiny_and_huge", "mostly_invalid"])
+def test_many_query_rerank_degenerate_score_rows(misa, shape):
+    """Rows whose dense scores tie massively, span many binades or are mostly -inf: the selection
+    inside the kernel must stay exact (ties to the lower position) on every route it can take."""
+    seed, L, kc, k = 9950, 4000, 3000, 700
+    rng = np.random.default_rng(seed)
+    wl, inp = _problem(seed, "bf16", "bf16", 64, L)
+    K = inp["K"]                                           # [1, L, d] bf16 bit patterns
+    if shape == "constant":
+        K[0, :] = K[0, 17]                                 # every key the same row: all scores of a query equal
+    elif shape == "three_values":
+        K[0, :] = K[0, rng.integers(0, 3, L)]              # three distinct keys: ~1000 equal scores each
+    elif shape == "outliers":
+        big = rng.choice(L, size=40, replace=False)
+        K[0, big] = _times_power_of_two(K[0, big], 12)     # forty keys 4096 times larger
+    elif shape == "tiny_and_huge":
+        e = rng.integers(-30, 31, L)                       # keys spread over sixty binades
+        K[0] = np.stack([_times_power_of_two(K[0, i], int(e[i])) for i in range(L)])
+    dv = misa.to_device(inp)
+    p = dv["problem"]
+    cand = _candidates(rng, ROWS, L, kc, full=(shape != "mostly_invalid"))
+    if shape == "mostly_invalid":
+        cand[:, :, 200:] = -1                              # fewer valid candidates than k
+        cand[0, 3, :] = -1                                 # none at all
+    dcand = torch.from_numpy(cand).cuda()
+    idx, val = _rerank(misa, p, dv, dcand, kc, k)
+    idx2, val2 = _rerank_in_pieces(misa, p, dv, dcand, kc, k)
+    assert torch.equal(idx, idx2)
+    assert torch.equal(val, val2)
+    sample = [0, 3, ROWS - 1] + rng.choice(ROWS, size=9, replace=False).tolist()
+    _check_rows_against_oracle(inp, cand, idx.cpu().numpy(), val.cpu().numpy(), k, sample, f"fused rerank {shape}")
+
+
+def test_longest_list_the_kernel_takes(misa):
+    # k' = 8192 (the limit of the one-kernel path) and k' = 8193 (the first length beyond it) agree
+    # with the oracle on sampled rows
+    seed, L = 9970, 12000
+    rng = np.random.default_rng(seed)
+    wl, inp = _problem(seed, "e4m3", "bf16", 64, L)
+    dv = misa.to_device(inp)
+    p = dv["problem"]
+    for kc, k in ((8192, 2048), (8193, 2048)):
+        cand = _candidates(rng, ROWS, L, kc, full=True)
+        idx, val = _rerank(misa, p, dv, torch.from_numpy(cand).cuda(), kc, k)
+        sample = [0, ROWS - 1] + rng.choice(ROWS, size=6, replace=False).tolist()
+        _check_rows_against_oracle(inp, cand, idx.cpu().numpy(), val.cpu().numpy(), k, sample, f"rerank k'={kc}")

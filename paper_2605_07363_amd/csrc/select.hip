@@ -214,6 +214,7 @@ __global__ __launch_bounds__(NT) void select_rows_kernel(
   __shared__ uint32_t bkey[64];
   __shared__ int bidx[64];
   __shared__ int b_len;
+  __shared__ int brank[64];       // entries of the boundary list that rank before an entry
   __shared__ int seg_first[65];   // offset of a range's segment in the row's list
   __shared__ int seg_pre[65];     // entries of the ranges before it (compact numbering of the row's entries)
   __shared__ int seg_bad;
@@ -279,6 +280,7 @@ __global__ __launch_bounds__(NT) void select_rows_kernel(
   }
   for (int i = tid; i < nwords; i += NT) sel[i] = 0;
   if (tid == 0) b_len = 0;
+  if (tid < 64) brank[tid] = 0;
   zero_hist_n<NT>(hist);  // ends with a barrier
   auto mark = [&](int e) { atomicOr(&sel[e >> 5], 1u << (e & 31)); };
 
@@ -314,16 +316,23 @@ __global__ __launch_bounds__(NT) void select_rows_kernel(
         if (b >= 0) { bkey[b] = ek[u]; bidx[b] = ei[u]; }
       }
       __syncthreads();
-      if (tid < nb) {
-        const uint32_t key = bkey[tid];
-        const int e = bidx[tid];
-        int rank = 0;
-        for (int j = 0; j < nb; ++j) {
-          const uint32_t kj = bkey[j];
-          rank += (kj > key || (kj == key && bidx[j] < e)) ? 1 : 0;
+      {
+        // all pairs of the (at most 64) boundary entries, spread over the block: thread t compares
+        // entry t % 64 with its share of the others
+        constexpr int JP = 64 / (NT / 64);
+        const int i = tid & 63, j0 = (tid >> 6) * JP;
+        if (i < nb && j0 < nb) {
+          const uint32_t key = bkey[i];
+          const int e = bidx[i];
+          int part = 0;
+#pragma unroll
+          for (int j = j0; j < j0 + JP; ++j)
+            part += (j < nb && (bkey[j] > key || (bkey[j] == key && bidx[j] < e))) ? 1 : 0;
+          if (part) atomicAdd(&brank[i], part);
         }
-        if (rank < need) mark(e);
       }
+      __syncthreads();
+      if (tid < nb && brank[tid] < need) mark(bidx[tid]);
       done = true;
     } else {
       __syncthreads();

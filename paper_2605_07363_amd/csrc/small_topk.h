@@ -35,6 +35,7 @@ struct SmallTopkLds {
   uint32_t eq[kSmallTopkWords];
   int wpre[kSmallTopkWords];         // selected positions in the bitmap words before a word
   uint2 few[kSmallTopkFew];          // (key, position) of the entries of the threshold bin
+  int few_rank[kSmallTopkFew];       // entries of that list that rank before an entry
   int scan[32];
   int thr[4];
   uint32_t red[3 * 4];
@@ -72,7 +73,10 @@ __device__ __forceinline__ void small_row_topk(const int* sc, int n, int k, cons
   }
   if (lane == 0) { L.red[wave] = (uint32_t)selectable; L.red[4 + wave] = kmax; L.red[8 + wave] = kmin; }
   if (tid == 0) L.few_len = 0;
-  if (tid < kSmallTopkFew) L.few[tid] = make_uint2(0u, 0u);   // padding of the brute-force list: key 0 ranks below every live key
+  if (tid < kSmallTopkFew) {
+    L.few[tid] = make_uint2(0u, 0u);   // padding of the brute-force list: key 0 ranks below every live key
+    L.few_rank[tid] = 0;
+  }
   __syncthreads();
   selectable = (int)(L.red[0] + L.red[1] + L.red[2] + L.red[3]);
   kmax = max(max(L.red[4], L.red[5]), max(L.red[6], L.red[7]));
@@ -159,18 +163,24 @@ __device__ __forceinline__ void small_row_topk(const int* sc, int n, int k, cons
   }
   __syncthreads();
   if (mode == kBrute) {
-    // the nb entries of the threshold bin, ranked by score, then position
-    if (tid < nb) {
-      const uint2 mine = L.few[tid];
-      int rank = 0;
-      for (int j0 = 0; j0 < nb; j0 += 8) {     // (the list is padded with entries that rank below all)
+    // the nb entries of the threshold bin, ranked by score, then position: all pairs, thread t
+    // comparing entry t % 64 with a quarter of the list (padded with entries that rank below all)
+    {
+      constexpr int JP = kSmallTopkFew / (NT / 64);
+      const int i = tid & 63, j0 = (tid >> 6) * JP;
+      const uint2 mine = L.few[i];
+      int part = 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const uint2 o = L.few[j0 + j];
-          rank += (o.x > mine.x || (o.x == mine.x && o.y < mine.y)) ? 1 : 0;
-        }
+      for (int j = j0; j < j0 + JP; ++j) {
+        const uint2 o = L.few[j];
+        part += (o.x > mine.x || (o.x == mine.x && o.y < mine.y)) ? 1 : 0;
       }
-      if (rank < need) atomicOr(&L.sel[mine.y >> 5], 1u << (mine.y & 31));
+      if (part) atomicAdd(&L.few_rank[i], part);
+    }
+    __syncthreads();
+    if (tid < nb && L.few_rank[tid] < need) {
+      const uint32_t e = L.few[tid].y;
+      atomicOr(&L.sel[e >> 5], 1u << (e & 31));
     }
     __syncthreads();
   } else if (mode == kTies) {

@@ -11,7 +11,8 @@ The default run times the long-decode workload c3 (the HBM half of the metric:
 `value`, `roofline`) and then, in the same process, the MISA-dagger prefill
 workload c4 at the same L = 131072 (the matrix-core half: object `prefill`)
 and the single-stage prefill chunk c2 (object `prefill_single_stage`), each
-once as separate calls and once with scoring and top-k fused.  Every number in the
+once as separate calls and once with scoring and top-k fused, and c4 once more with
+fp8 queries on the fp8 matrix instruction (object `prefill_fp8_queries`).  Every number in the
 line is measured by this run except where a field says otherwise.
 """
 from __future__ import annotations
@@ -376,9 +377,11 @@ def main() -> int:
         pargs = copy.copy(args)
         pargs.steps, pargs.warmup = min(args.steps, 10), min(args.warmup, 2)
 
-        def prefill_object(name):
-            two = measure(pargs, name, False, False)
-            one = measure(pargs, name, True, False)
+        def prefill_object(name, fp8_queries=False):
+            margs = copy.copy(pargs)
+            margs.fp8_queries = fp8_queries
+            two = measure(margs, name, False, False)
+            one = measure(margs, name, True, False)
             r2, r1 = roofline_of(two, peaks), roofline_of(one, peaks)
             w = two["wl"]
             obj = {
@@ -405,6 +408,10 @@ def main() -> int:
 
         out["prefill"] = prefill_object("c4")
         out["prefill_single_stage"] = prefill_object("c2")
+        # the same MISA-dagger prefill with the queries quantised to e4m3 as well (the paper notes that
+        # DSA runs its indexer in FP8): both operands stay fp8 codes, products on the fp8 matrix
+        # instruction, priced against the fp8 peak
+        out["prefill_fp8_queries"] = prefill_object("c4", fp8_queries=True)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, m["inp"])

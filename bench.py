@@ -182,6 +182,23 @@ def measure(args, name: str, fused: bool, main_line: bool) -> dict:
     dt = time.perf_counter() - t0
     eager_ms = dt / args.steps * 1e3
 
+    # The per-stage durations reported below come from a second pass of the same eager steps,
+    # enqueued behind a run of plain read kernels: the host has then queued every event and
+    # launch before the GPU reaches them, so an event pair brackets its kernels back to back and
+    # not the host's launch latency on an idle stream (which added 2-8 us to a 97 us kernel,
+    # depending on the machine's host).
+    blocker = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+    blocker_sink = torch.zeros(8 * 1024 * 256, dtype=torch.float32, device="cuda")
+    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in stage_names] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    for _ in range(int(1.5 * args.steps * eager_ms / 0.085) + 8):     # one read of 512 MiB takes about 0.085 ms
+        misa.probe_hbm_read(blocker, blocker_sink)
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    del blocker, blocker_sink
+
     # Timed region proper: the same step (all calls, same buffers) captured once per
     # key-cache copy into a HIP graph and replayed, which removes the launch gaps
     # between the 5-10 short kernels of a step.  Every replay is checked against
@@ -356,6 +373,8 @@ def main() -> int:
                    "key_cache_bytes": m["key_bytes"], "key_buffers_rotated": m["n_rot"]},
         "launch": "hip-graph replay of the whole step" if m["use_graph"] else "eager",
         "eager_ms_per_step": m["eager_ms"],
+        "stage_timing": "HIP events around every call of eager steps that were queued behind plain read kernels "
+                        "(the GPU never waits for the host between an event and the launch it brackets)",
         "stage_ms": m["stage_ms"],
         "ms_per_step_excl_pool": m["ms_per_step_excl_pool"],
         "score_stage_pairs_per_s": m["pairs"] / (m["stage_ms"]["select" if m["fused"] else "score"] * 1e-3),

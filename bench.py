@@ -301,6 +301,12 @@ def roofline_of(m: dict, peaks: dict) -> dict:
                 "peak": peak, "unit": "TFLOP/s", "frac": flops / score_s / 1e12 / peak, "traffic": None,
                 "algorithmic_flops": flops, "avg_launch_ms": score_s * 1e3, "matrix_dtype": kind}
         roof["measured_peak"] = peaks["mfma_bf16_TFLOPs"] * (2.0 if kind == "fp8" else 1.0)
+        if kind == "bf16":
+            # the same probe on Gaussian bf16 operands of the workloads' scale: the rate the matrix pipe
+            # sustains on such data with nothing else in the kernel (the clock the chip holds depends
+            # on the operand values)
+            roof["measured_peak_gaussian_operands"] = peaks["mfma_bf16_gaussian_operands_TFLOPs"]
+            roof["frac_of_measured_gaussian_operands"] = roof["achieved"] / peaks["mfma_bf16_gaussian_operands_TFLOPs"]
         if kind == "fp8":
             roof["measured_peak_note"] = "2 x the measured bf16 matrix rate (the probe issues bf16 instructions)"
     roof["frac_of_measured"] = roof["achieved"] / roof["measured_peak"]

@@ -375,11 +375,20 @@ misa_status misa_convert_queries(const misa_problem* p, const void* Q, void* Q_b
  * duration is the achievable dense bf16 matrix rate at the clock the chip sustains.
  *   sink   out  device, workgroups * 256 floats
  *   flops  out  HOST pointer or NULL: floating-point operations of the launch
- * Both enqueue on `stream` and return; time them with events.
+ * The operands are constants (1.0 x {0.5, 1.0}).
+ *
+ * misa_probe_mfma_bf16_operands: the same loop on operands the caller supplies.  The matrix rate
+ * MI355X sustains depends on the operand VALUES (the clock it holds drops as more bits toggle
+ * per product), so the rate reachable on data like a workload's is measured with such data.
+ *   operands  in  device, 16-byte aligned, 2048 bytes: 64 x 16 bytes (eight bf16) = fragment a
+ *                 of lanes 0..63, then 64 x 16 bytes = fragment b; every wavefront uses the same
+ * All three enqueue on `stream` and return; time them with events.
  */
 misa_status misa_probe_hbm_read(const void* buf, size_t bytes, void* sink, void* stream);
 misa_status misa_probe_mfma_bf16(int32_t workgroups, int32_t iters, float* sink, double* flops,
                                  void* stream);
+misa_status misa_probe_mfma_bf16_operands(int32_t workgroups, int32_t iters, const void* operands,
+                                          float* sink, double* flops, void* stream);
 
 #ifdef __cplusplus
 }

@@ -422,8 +422,19 @@ misa_status misa_probe_mfma_bf16(int32_t workgroups, int32_t iters, float* sink,
   if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 24))
     return fail(MISA_ERR_INVALID_ARG, "need 1 <= workgroups <= 2^20 and 1 <= iters <= 2^24");
   if (flops) *flops = (double)workgroups * 4.0 * (double)iters * misa::kProbeMfmaFlopsPerWaveIter;
-  return hip_result(misa::launch_probe_mfma(workgroups, iters, sink, (hipStream_t)stream),
+  return hip_result(misa::launch_probe_mfma(workgroups, iters, nullptr, sink, (hipStream_t)stream),
                     "misa_probe_mfma_bf16 launch");
+}
+
+misa_status misa_probe_mfma_bf16_operands(int32_t workgroups, int32_t iters, const void* operands,
+                                          float* sink, double* flops, void* stream) {
+  if (!sink || !operands) return fail(MISA_ERR_INVALID_ARG, "sink or operands is NULL");
+  if (!aligned(operands, 16)) return fail(MISA_ERR_INVALID_ARG, "operands must be 16-byte aligned");
+  if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 24))
+    return fail(MISA_ERR_INVALID_ARG, "need 1 <= workgroups <= 2^20 and 1 <= iters <= 2^24");
+  if (flops) *flops = (double)workgroups * 4.0 * (double)iters * misa::kProbeMfmaFlopsPerWaveIter;
+  return hip_result(misa::launch_probe_mfma(workgroups, iters, operands, sink, (hipStream_t)stream),
+                    "misa_probe_mfma_bf16_operands launch");
 }
 
 }  // extern "C"

@@ -115,6 +115,7 @@ hipError_t launch_widen_queries(const void* q8, void* q16, size_t n_elems, hipSt
 // Probes for the roofline report (peaks.hip).
 constexpr int kProbeMfmaFlopsPerWaveIter = 4 * 2 * 32 * 32 * 16;
 hipError_t launch_probe_read(const void* buf, size_t bytes, void* sink, hipStream_t st);
-hipError_t launch_probe_mfma(int workgroups, int iters, float* sink, hipStream_t st);
+// operands: nullptr (constant operands) or 2048 bytes on the device: fragment a, then fragment b, of the 64 lanes
+hipError_t launch_probe_mfma(int workgroups, int iters, const void* operands, float* sink, hipStream_t st);
 
 }  // namespace misa

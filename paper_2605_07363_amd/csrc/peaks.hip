@@ -30,12 +30,20 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const uint4* __restrict
 // other).  No memory traffic but the final store.
 constexpr int kProbeMfmaPerIter = 4;
 
-__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* __restrict__ sink) {
-  union { bf16x8 v; uint32_t u[4]; } a, b;
+// operands == nullptr: constant operands (1.0 x {0.5, 1.0}).  Otherwise lane l of every wavefront
+// takes its two fragments from operands[l] and operands[64 + l] (16 bytes each): the rate the
+// chip sustains depends on the operand values (its clock drops as more bits toggle per product).
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, const uint4* __restrict__ operands,
+                                                         float* __restrict__ sink) {
+  union { bf16x8 v; uint32_t u[4]; uint4 q; } a, b;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     a.u[i] = 0x3F803F80u;                                  // bf16 1.0, 1.0
     b.u[i] = (threadIdx.x & 1) ? 0x3F803F80u : 0x3F003F00u;  // 1.0 or 0.5
+  }
+  if (operands) {
+    a.q = operands[threadIdx.x & 63];
+    b.q = operands[64 + (threadIdx.x & 63)];
   }
   f32x16 acc[kProbeMfmaPerIter];
 #pragma unroll
@@ -63,8 +71,8 @@ hipError_t launch_probe_read(const void* buf, size_t bytes, void* sink, hipStrea
   return hipGetLastError();
 }
 
-hipError_t launch_probe_mfma(int workgroups, int iters, float* sink, hipStream_t st) {
-  probe_mfma_kernel<<<workgroups, 256, 0, st>>>(iters, sink);
+hipError_t launch_probe_mfma(int workgroups, int iters, const void* operands, float* sink, hipStream_t st) {
+  probe_mfma_kernel<<<workgroups, 256, 0, st>>>(iters, static_cast<const uint4*>(operands), sink);
   return hipGetLastError();
 }
 

@@ -74,6 +74,8 @@ lib.misa_probe_hbm_read.restype = ctypes.c_int
 lib.misa_probe_hbm_read.argtypes = [_V, ctypes.c_size_t, _V, _V]
 lib.misa_probe_mfma_bf16.restype = ctypes.c_int
 lib.misa_probe_mfma_bf16.argtypes = [ctypes.c_int32, ctypes.c_int32, _V, ctypes.POINTER(ctypes.c_double), _V]
+lib.misa_probe_mfma_bf16_operands.restype = ctypes.c_int
+lib.misa_probe_mfma_bf16_operands.argtypes = [ctypes.c_int32, ctypes.c_int32, _V, _V, ctypes.POINTER(ctypes.c_double), _V]
 lib.misa_rerank.restype = ctypes.c_int
 lib.misa_rerank.argtypes = [_P, _V, _V, _V, _V, _V, ctypes.c_int32, ctypes.c_int32, _V, _V, _V,
                             ctypes.c_size_t, _V]
@@ -250,25 +252,37 @@ def probe_hbm_read(buf, sink, nbytes: Optional[int] = None) -> int:
     return nbytes
 
 
-def probe_mfma_bf16(workgroups: int, iters: int, sink) -> float:
-    """Enqueues the matrix-instruction probe; returns its floating-point operation count."""
+def probe_mfma_bf16(workgroups: int, iters: int, sink, operands=None) -> float:
+    """Enqueues the matrix-instruction probe; returns its floating-point operation count.
+    operands: None (constant operands) or a device tensor of 1024 bf16 (fragments a, then b, of the 64 lanes)."""
     if sink.numel() < workgroups * 256 or sink.dtype != torch.float32:
         raise ValueError("sink must hold workgroups * 256 floats")
     flops = ctypes.c_double(0.0)
-    _check(lib.misa_probe_mfma_bf16(workgroups, iters, _ptr(sink), ctypes.byref(flops), _stream()))
+    if operands is None:
+        _check(lib.misa_probe_mfma_bf16(workgroups, iters, _ptr(sink), ctypes.byref(flops), _stream()))
+    else:
+        if operands.numel() * operands.element_size() < 2048 or not operands.is_contiguous():
+            raise ValueError("operands must hold 2048 contiguous bytes")
+        _check(lib.misa_probe_mfma_bf16_operands(workgroups, iters, _ptr(operands), _ptr(sink),
+                                                 ctypes.byref(flops), _stream()))
     return flops.value
 
 
 def measured_peaks(device="cuda", repeats: int = 10) -> dict:
     """Achievable HBM read rate (GB/s) and dense bf16 matrix rate (TFLOP/s) of this GPU, each the
-    best of `repeats` event-timed bursts of launches of the library's probes (512 MiB read; ~1e13 flop)."""
+    best of `repeats` event-timed bursts of launches of the library's probes (512 MiB read; ~1e13 flop).
+    The matrix rate is taken twice: on the probe's constant operands, and on seeded Gaussian bf16
+    operands of the workloads' scale (sigma = 1/sqrt(128)), for which the chip holds a lower clock."""
     buf = torch.empty(512 << 20, dtype=torch.uint8, device=device)
     buf.fill_(1)
     sink = torch.zeros(8 * 1024 * 256, dtype=torch.float32, device=device)
     cus = torch.cuda.get_device_properties(device).multi_processor_count
     wgs, iters = cus * 8, 2048
+    g = torch.Generator(device="cpu")
+    g.manual_seed(20260507)
+    gauss = (torch.randn(1024, generator=g) * (128 ** -0.5)).to(torch.bfloat16).to(device)
     out = {}
-    for name in ("hbm_read_GBps", "mfma_bf16_TFLOPs"):
+    for name in ("hbm_read_GBps", "mfma_bf16_TFLOPs", "mfma_bf16_gaussian_operands_TFLOPs"):
         best = float("inf")
         amount = 0.0
         burst = 8 if name.startswith("hbm") else 2   # launches between the two events: gaps and event cost amortised
@@ -276,7 +290,8 @@ def measured_peaks(device="cuda", repeats: int = 10) -> dict:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(burst):
-                amount = probe_hbm_read(buf, sink) if name.startswith("hbm") else probe_mfma_bf16(wgs, iters, sink)
+                amount = probe_hbm_read(buf, sink) if name.startswith("hbm") else \
+                    probe_mfma_bf16(wgs, iters, sink, gauss if "gaussian" in name else None)
             e1.record()
             e1.synchronize()
             best = min(best, e0.elapsed_time(e1) / burst)

@@ -20,7 +20,7 @@ def test_every_declared_symbol_is_exported(misa):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(misa_[a-z0-9_]+)\s*\(", header))
     assert {"misa_pool_keys", "misa_route_heads", "misa_score_tokens", "misa_topk", "misa_rerank", "misa_select_tokens", "misa_hisa_select", "misa_block_sparse_select", "misa_pool_keys_update", "misa_route_heads_proxy",
-            "misa_probe_hbm_read", "misa_probe_mfma_bf16", "misa_convert_queries",
+            "misa_probe_hbm_read", "misa_probe_mfma_bf16", "misa_probe_mfma_bf16_operands", "misa_convert_queries",
             "misa_workspace_bytes", "misa_last_error", "misa_version"} <= names
     for n in names:
         assert hasattr(misa.lib, n), f"{n} declared in misa.h but not exported"
@@ -116,6 +116,9 @@ def test_page_table_and_probe_arguments(misa):
     assert misa.lib.misa_probe_mfma_bf16(0, 1, FAKE, None, None) == INVALID
     assert misa.lib.misa_probe_mfma_bf16(1, 0, FAKE, None, None) == INVALID
     assert misa.lib.misa_probe_mfma_bf16(1, 1, None, None, None) == INVALID
+    assert misa.lib.misa_probe_mfma_bf16_operands(1, 1, None, FAKE, None, None) == INVALID
+    assert misa.lib.misa_probe_mfma_bf16_operands(1, 1, ctypes.c_void_p(0x1008), FAKE, None, None) == INVALID
+    assert misa.lib.misa_probe_mfma_bf16_operands(0, 1, FAKE, FAKE, None, None) == INVALID
 
 
 def test_paginate_places_every_key_where_the_page_table_says(misa):

@@ -461,6 +461,14 @@ def test_measurement_probes_report_plausible_rates(misa):
     # operands are 1.0 x {0.5, 1.0}: every accumulator element is 3 iterations x 16 products
     got = sink.cpu().numpy()
     assert set(np.unique(got).tolist()) <= {4 * 16 * 3 * 16 * 0.5, 4 * 16 * 3 * 16 * 1.0, 4 * 16 * 3 * 16 * 0.75}
+    # the same loop on supplied operands: a = 2.0, b = 0.25 everywhere, so every product is 0.5
+    ops = torch.cat([torch.full((512,), 2.0), torch.full((512,), 0.25)]).to(torch.bfloat16).cuda()
+    sink.zero_()
+    assert misa.probe_mfma_bf16(1, 3, sink, ops) == flops
+    torch.cuda.synchronize()
+    assert np.all(sink.cpu().numpy() == 4 * 16 * 3 * 16 * 0.5)
+    # Gaussian operands make the chip hold a lower clock: a lower rate than on the constant operands
+    assert 500.0 < peaks["mfma_bf16_gaussian_operands_TFLOPs"] < 1.02 * peaks["mfma_bf16_TFLOPs"]
 
 
 # --------------------------------------------------------------------- random top-k rows

@@ -175,3 +175,48 @@ def test_longest_list_the_kernel_takes(misa):
         idx, val = _rerank(misa, p, dv, torch.from_numpy(cand).cuda(), kc, k)
         sample = [0, ROWS - 1] + rng.choice(ROWS, size=6, replace=False).tolist()
         _check_rows_against_oracle(inp, cand, idx.cpu().numpy(), val.cpu().numpy(), k, sample, f"rerank k'={kc}")
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_many_query_rerank_over_several_ragged_sequences(misa, paged):
+    # 3 sequences x 400 queries (1200 rows: the one-kernel path), ragged lengths, optionally a page
+    # pool; every sequence alone (400 rows: dense scores + row top-k) must give the same bits
+    seed, L, kc, k, n_seq, n_q = 9990, 2500, 1500, 300, 3, 400
+    rng = np.random.default_rng(seed)
+    wl = WL.scaled(WL.WORKLOADS["c2"], n_seq=n_seq, L=L, n_q=n_q, H=64, h=1, B=64, k=1, k_cand=0,
+                   k_dtype="e4m3", q_dtype="bf16", needles=6, name="rrf_multi")
+    inp = WL.make_inputs(wl, seed=seed, seq_len=np.array([L, 1700, 900], dtype=np.int32))
+    dv = misa.to_device(inp)
+    if paged:
+        dv = misa.paginate(dv, 64, seed=seed)
+    p = dv["problem"]
+    cand = np.concatenate([_candidates(rng, n_q, L, kc) for _ in range(n_seq)], axis=0)
+    dcand = torch.from_numpy(cand).cuda()
+    idx = torch.full((n_seq, n_q, k), -9, dtype=torch.int32, device="cuda")
+    val = torch.full((n_seq, n_q, k), 7.0, dtype=torch.float32, device="cuda")
+    misa.rerank(p, dv["Q"], dv["W"], dv["K"], dv["kscale"], dcand, kc, k, idx, val,
+                misa.alloc_workspace(p, misa.OP_RERANK, kc))
+    torch.cuda.synchronize()
+    for s in range(n_seq):
+        ps = replace(p, n_seq=1, seq_len=p.seq_len[s:s + 1].contiguous(),
+                     page_table=None if p.page_table is None else p.page_table[s:s + 1].contiguous())
+        Ks, kss = (dv["K"], dv["kscale"]) if paged else (dv["K"][s:s + 1], dv["kscale"][s:s + 1])
+        i1 = torch.empty((1, n_q, k), dtype=torch.int32, device="cuda")
+        v1 = torch.empty((1, n_q, k), dtype=torch.float32, device="cuda")
+        misa.rerank(ps, dv["Q"][s:s + 1], dv["W"][s:s + 1], Ks, kss, dcand[s:s + 1], kc, k, i1, v1,
+                    misa.alloc_workspace(ps, misa.OP_RERANK, kc))
+        torch.cuda.synchronize()
+        assert torch.equal(idx[s:s + 1], i1), f"sequence {s}"
+        assert torch.equal(val[s:s + 1], v1), f"sequence {s}"
+    ih, vh = idx.cpu().numpy(), val.cpu().numpy()
+    for s in range(n_seq):
+        for t in [0, n_q - 1] + rng.choice(n_q, size=4, replace=False).tolist():
+            K, q, w, n = oracle_view(inp, s, t)
+            dense = O.dsa_scores(q, w, K, n) if n else np.zeros(0)
+            valid = np.array(sorted(c for c in cand[s, t] if 0 <= c < n), dtype=np.int64)
+            ke = min(k, valid.shape[0])
+            got = ih[s, t]
+            assert np.all(got[ke:] == -1) and np.all(np.diff(got[:ke]) > 0)
+            pos = np.searchsorted(valid, got[:ke])
+            check_index_set(np.concatenate([pos, np.full(k - ke, -1, dtype=pos.dtype)]), dense[valid], k, f"multi {s},{t}")
+            assert_scores_close(vh[s, t, :ke], dense[got[:ke]], f"multi values {s},{t}")

@@ -1319,7 +1319,7 @@ template <int KDT, bool Q8>
 static hipError_t launch_gather(const Prob& p, const void* Q, const float* W, const void* K,
                                 const float* kscale, const int* cand, int k_cand, float* out,
                                 hipStream_t st) {
-  // pieces of 512 .. kGatherChunk candidates (a step of the four wavefronts covers 128): halved
+  // pieces of 512 .. kGatherChunk candidates (a step of the four wavefronts covers 128 or 256): halved
   // while fewer than 1024 workgroups would result
   int chunk = kGatherChunk;
   const long long rows = (long long)p.n_q * p.n_seq;
@@ -1335,12 +1335,11 @@ static hipError_t launch_gather(const Prob& p, const void* Q, const float* W, co
       default: GO(4); break;
     }
 #undef GO
-    return hipGetLastError();
-  }
-  if (p.H <= 32)
+  } else if (p.H <= 32) {
     score_gather_kernel<KDT, 1, Q8, false><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, chunk, out, 0, nullptr, nullptr);
-  else
+  } else {
     score_gather_kernel<KDT, 2, Q8, false><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, chunk, out, 0, nullptr, nullptr);
+  }
   return hipGetLastError();
 }
 
@@ -1369,12 +1368,11 @@ static hipError_t launch_gather_topk(const Prob& p, const void* Q, const float* 
       default: GO(4); break;
     }
 #undef GO
-    return hipGetLastError();
-  }
-  if (p.H <= 32)
+  } else if (p.H <= 32) {
     score_gather_kernel<KDT, 1, Q8, true><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, chunk, nullptr, k, idx, val);
-  else
+  } else {
     score_gather_kernel<KDT, 2, Q8, true><<<grid, 256, 0, st>>>(p, q, W, K, kscale, cand, k_cand, chunk, nullptr, k, idx, val);
+  }
   return hipGetLastError();
 }
 

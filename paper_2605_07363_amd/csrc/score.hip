@@ -471,6 +471,15 @@ __device__ __forceinline__ void score_tile_body(
   // Staging registers of the next key tile (global -> registers -> LDS).  Thread
   // tid moves the 16-byte chunks tid + 256 i of the tile.
   constexpr int CPR = ROW_BYTES / 16;  // chunks per key row
+  // Which chunk of the tile a thread stages: chunk stid + 256 i.  fp8 rows that are widened on
+  // the way (each 16-byte chunk becomes two LDS slots) permute the chunks inside every group of
+  // 16 lanes (= two key rows), so that eight consecutive lanes cover four chunks of one row and
+  // the same four of the next: their LDS stores then fall into eight different 16-byte bank
+  // groups (rows are 17 slots apart), where eight chunks of one row hit only the four even ones
+  // (measured: 24 % of this kernel's LDS cycles were bank conflicts, none with bf16 rows).
+  const int stid = (KDT == MISA_FP8_E4M3 && !Q8)
+                       ? ((tid & ~15) | (((tid >> 2) & 1) << 3) | ((tid & 3) + 4 * ((tid >> 3) & 1)))
+                       : tid;
   uint4 st0 = make_uint4(0, 0, 0, 0), st1 = st0, st2 = st0, st3 = st0;
   float st_scale = 1.f;
   // A contiguous, unsampled cache is read through a buffer descriptor of the sequence's keys:
@@ -479,7 +488,7 @@ __device__ __forceinline__ void score_tile_body(
   // (the descriptor's range check) instead of being clamped per lane.
   constexpr bool LINEAR = !SAMPLE && !PAGED;
   const BufferRsrc krsrc = make_rsrc(kbase, (uint32_t)p.L * (uint32_t)ROW_BYTES);
-  uint32_t koff = (uint32_t)k_begin * ROW_BYTES + (uint32_t)tid * 16u;  // next tile to request
+  uint32_t koff = (uint32_t)k_begin * ROW_BYTES + (uint32_t)stid * 16u;  // next tile to request
   // Cache row of key j of tile space (clamped into the cache).  Sampling takes key
   // 16 j + (top four bits of a multiplicative hash of j) of every group of 16.
   // With a page table the row is the one in the page pool and kbase the pool itself.
@@ -500,18 +509,18 @@ __device__ __forceinline__ void score_tile_body(
       }                                                                                           \
       koff += kKT * ROW_BYTES;                                                                    \
     } else {                                                                                      \
-      st0 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + tid / CPR) * ROW_BYTES + (tid % CPR) * 16); \
-      st1 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 256) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
+      st0 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + stid / CPR) * ROW_BYTES + (stid % CPR) * 16); \
+      st1 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (stid + 256) / CPR) * ROW_BYTES + (stid % CPR) * 16); \
       if (NLD == 4) {                                                                             \
-        st2 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 512) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
-        st3 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (tid + 768) / CPR) * ROW_BYTES + (tid % CPR) * 16); \
+        st2 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (stid + 512) / CPR) * ROW_BYTES + (stid % CPR) * 16); \
+        st3 = *reinterpret_cast<const uint4*>(kbase + key_row((k0) + (stid + 768) / CPR) * ROW_BYTES + (stid % CPR) * 16); \
       }                                                                                           \
     }                                                                                             \
     if (KDT == MISA_FP8_E4M3 && tid < kKT) st_scale = kscale[(PAGED ? (size_t)0 : (size_t)seq * p.L) + key_row((k0) + tid)]; \
   } while (0)
-  // registers -> LDS (bf16, padded rows): chunk tid + 256 i is chunk tid % CPR of row
-  // tid / CPR + (256 / CPR) i, so the four writes differ by a constant
-  uint4* const lds_put = &ktile[0][0] + (tid / CPR) * KP + (KDT == MISA_BF16 || Q8 ? tid % CPR : 2 * (tid % CPR));
+  // registers -> LDS (bf16, padded rows): chunk stid + 256 i is chunk stid % CPR of row
+  // stid / CPR + (256 / CPR) i, so the four writes differ by a constant
+  uint4* const lds_put = &ktile[0][0] + (stid / CPR) * KP + (KDT == MISA_BF16 || Q8 ? stid % CPR : 2 * (stid % CPR));
   auto put_chunk = [&](int b, int i, const uint4& v) {
     uint4* dst = lds_put + b * (kKT * KP) + i * ((256 / CPR) * KP);
     if (KDT == MISA_BF16 || Q8) {

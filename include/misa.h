@@ -259,7 +259,7 @@ misa_status misa_topk(const misa_problem* p, const float* S, int32_t k, int32_t*
  * misa_candidate; heads == NULL: Eq. dsa_score then Eq. dsa_topk).  Writes
  * exactly what misa_score_tokens followed by misa_topk would write to idx and
  * val, but for many-query problems (bf16 queries, bf16 or FP8 keys, n_q >= 8,
- * k <= 8192, L >= 4096) the [n_seq, n_q, L] score matrix is not produced:
+ * k <= 8192, L >= 4096, p->h >= 3) the [n_seq, n_q, L] score matrix is not produced:
  * a 1/16 sample of the keys gives a per-row threshold, a second scoring pass
  * keeps only the scores that reach it, and the exact top-k is taken from
  * those.  Rows for which the threshold turns out too high or too low are

@@ -220,3 +220,27 @@ def test_many_query_rerank_over_several_ragged_sequences(misa, paged):
             pos = np.searchsorted(valid, got[:ke])
             check_index_set(np.concatenate([pos, np.full(k - ke, -1, dtype=pos.dtype)]), dense[valid], k, f"multi {s},{t}")
             assert_scores_close(vh[s, t, :ke], dense[got[:ke]], f"multi values {s},{t}")
+
+
+def test_many_query_rerank_writes_only_its_outputs(misa):
+    # idx / val are windows of larger buffers filled with a sentinel: nothing outside them changes,
+    # and the candidate list (which the kernel overwrites in LDS, not in memory) stays as it was
+    seed, L, kc, k = 9995, 2000, 777, 129
+    rng = np.random.default_rng(seed)
+    wl, inp = _problem(seed, "e4m3", "bf16", 64, L)
+    dv = misa.to_device(inp)
+    p = dv["problem"]
+    cand = torch.from_numpy(_candidates(rng, ROWS, L, kc)).cuda()
+    before = cand.clone()
+    pad = 4096
+    ibuf = torch.full((pad + ROWS * k + pad,), -77, dtype=torch.int32, device="cuda")
+    vbuf = torch.full((pad + ROWS * k + pad,), 3.25, dtype=torch.float32, device="cuda")
+    idx = ibuf[pad:pad + ROWS * k].view(1, ROWS, k)
+    val = vbuf[pad:pad + ROWS * k].view(1, ROWS, k)
+    misa.rerank(p, dv["Q"], dv["W"], dv["K"], dv["kscale"], cand, kc, k, idx, val,
+                misa.alloc_workspace(p, misa.OP_RERANK, kc))
+    torch.cuda.synchronize()
+    assert torch.all(ibuf[:pad] == -77) and torch.all(ibuf[pad + ROWS * k:] == -77)
+    assert torch.all(vbuf[:pad] == 3.25) and torch.all(vbuf[pad + ROWS * k:] == 3.25)
+    assert torch.equal(cand, before)
+    assert torch.all(idx >= -1) and torch.all(idx < L)
